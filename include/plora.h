@@ -1,0 +1,153 @@
+/*
+ * plora.h - C ABI of the MI355X (gfx950) packed multi-LoRA linear layer, forward and backward.
+ *
+ * The layer (paper section 2.1 for LoRA, section 2.4 and appendix C.2 for packing): a frozen
+ * weight W in R^{d_in x d_out} is shared by n_adapters LoRA adapters (A_k in R^{d_in x r_k},
+ * B_k in R^{r_k x d_out}, multiplier scale_k = alpha_k / r_k chosen by the caller).  The tokens
+ * of all adapters are stacked along the sequence dimension into x in R^{T x d_in}; segment s
+ * holds rows seg_off[s] .. seg_off[s+1]-1 and belongs to adapter seg_adapter[s].  Row-vector
+ * convention throughout:
+ *
+ *   forward   y_t  = x_t W + scale_k (x_t A_k) B_k                 t in a segment of adapter k
+ *   backward  g_t  = scale_k dy_t B_k^T                            (appendix C.2, case 2)
+ *             dx_t = dy_t W^T + g_t A_k^T                          (case 4)
+ *             dA_k = sum_t x_t^T g_t                               (case 3)
+ *             dB_k = scale_k sum_t (x_t A_k)^T dy_t                (case 1)
+ *   W is frozen: no dW.
+ *
+ * General conventions
+ *   - All matrices are dense row-major: x[T][d_in], W[d_in][d_out], A_k[d_in][r_k],
+ *     B_k[r_k][d_out], y/dy[T][d_out], dx[T][d_in], dA_k[d_in][r_k], dB_k[r_k][d_out].
+ *   - Pointers marked DEVICE point to memory of the current HIP device; pointers marked HOST are
+ *     ordinary host memory that is read before the call returns (it may be freed afterwards).
+ *   - The caller owns every buffer.  The library allocates no device memory; temporary storage
+ *     comes from the caller's workspace (plora_workspace_bytes).
+ *   - Calls only enqueue work on the given HIP stream (a hipStream_t passed as void*; NULL is
+ *     the default stream) and never synchronise.  Two calls that share a workspace must be
+ *     ordered on one stream.
+ *   - Every argument is validated before anything is enqueued; on error nothing is launched and
+ *     no output is touched.  No exception or abort crosses this boundary.
+ *   - x, W, A_k, B_k, y, dy, dx have the element type desc->dtype.  The saved low-rank
+ *     activation h and the gradients dA_k, dB_k are always fp32.  bf16 results are rounded to
+ *     nearest-even from fp32 accumulators.
+ */
+#ifndef PLORA_H
+#define PLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PLORA_MAX_RANK      128   /* the paper's rank range ends at 128 (Table 1)              */
+#define PLORA_MAX_ADAPTERS  256
+#define PLORA_MAX_SEGMENTS 1024
+
+typedef enum {
+    PLORA_OK = 0,
+    PLORA_ERR_NULL = 1,         /* a required pointer is NULL                                   */
+    PLORA_ERR_SHAPE = 2,        /* T, d_in or d_out negative / zero / not a multiple of 8 (bf16)*/
+    PLORA_ERR_SEGMENTS = 3,     /* offsets do not start at 0, end at T, or decrease             */
+    PLORA_ERR_ADAPTER = 4,      /* adapter id outside [-1, n_adapters) or too many of them      */
+    PLORA_ERR_RANK = 5,         /* rank outside [1, PLORA_MAX_RANK]                             */
+    PLORA_ERR_ALIGN = 6,        /* a device pointer is not 16-byte aligned                      */
+    PLORA_ERR_WORKSPACE = 7,    /* workspace NULL or smaller than plora_workspace_bytes()       */
+    PLORA_ERR_UNSUPPORTED = 8,  /* unknown dtype                                                */
+    PLORA_ERR_HIP = 9           /* a HIP call failed (launch error)                             */
+} plora_status;
+
+typedef enum { PLORA_BF16 = 0, PLORA_F32 = 1 } plora_dtype;
+
+/* Shape and packing of one call.  Every array here is HOST memory. */
+typedef struct {
+    int64_t T;                    /* total tokens (rows of x); 0 is legal                       */
+    int64_t d_in;                 /* d of the paper                                             */
+    int64_t d_out;                /* k of the paper                                             */
+    int32_t n_seg;                /* number of segments, 0 only if T == 0                       */
+    int32_t n_adapters;
+    const int32_t *seg_off;       /* [n_seg+1] nondecreasing, seg_off[0]=0, seg_off[n_seg]=T    */
+    const int32_t *seg_adapter;   /* [n_seg] in [0, n_adapters), or -1: base weight only        */
+    const int32_t *rank;          /* [n_adapters] r_k in [1, PLORA_MAX_RANK]                    */
+    const float *scale;           /* [n_adapters] scale_k                                       */
+    int32_t dtype;                /* plora_dtype of x, W, A, B, y, dy, dx                       */
+} plora_desc;
+
+/* Text for a status code (static storage, never NULL). */
+const char *plora_status_string(plora_status st);
+
+/* Validates a description (host only, touches no device).  Returns PLORA_OK or the error. */
+plora_status plora_validate(const plora_desc *desc);
+
+/*
+ * Number of fp32 elements of the saved low-rank activation: sum over segments of
+ * (segment length x rank of its adapter); segments of adapter -1 contribute nothing.
+ * Segment s starts at the prefix sum of the segments before it and is stored [length][r_k]
+ * row-major.  Returns 0 for an invalid description.
+ */
+size_t plora_h_elems(const plora_desc *desc);
+
+/* Bytes of DEVICE workspace that plora_linear_fwd and plora_linear_bwd need for this
+ * description (the larger of the two; 256-byte aligned base expected).  0 if invalid. */
+size_t plora_workspace_bytes(const plora_desc *desc);
+
+/*
+ * Segment-packing metadata, computed on the host exactly as the launches use it (exposed so
+ * that it can be checked against brute force without a GPU).
+ *   h_off_out   [n_seg+1] element offset of each segment inside the saved activation
+ *               (int64 prefix sums of length x rank); may be NULL.
+ *   blocks_out  token blocks of at most block_rows rows that never straddle a segment, in row
+ *               order, 4 int32 each: {first row, number of rows, segment, adapter}; empty
+ *               segments produce none.  Written up to blocks_cap entries; may be NULL.
+ * Returns the number of token blocks (also when blocks_out is NULL or too small), or -1 for an
+ * invalid description or block_rows < 1.
+ */
+int64_t plora_build_metadata(const plora_desc *desc, int32_t block_rows, int64_t *h_off_out,
+                             int32_t *blocks_out, int64_t blocks_cap);
+
+/*
+ * Forward (section 2.4; y_t = x_t W + scale_k (x_t A_k) B_k).
+ *   x        DEVICE [T][d_in]
+ *   W        DEVICE [d_in][d_out]
+ *   A, B     HOST arrays of n_adapters DEVICE pointers, A[k] -> [d_in][r_k], B[k] -> [r_k][d_out]
+ *   y        DEVICE [T][d_out], overwritten
+ *   h_saved  DEVICE fp32 [plora_h_elems] or NULL; if given it receives x_t A_k for every
+ *            token (layout above) for later use by plora_linear_bwd
+ *   workspace, ws_bytes  DEVICE scratch, at least plora_workspace_bytes(desc)
+ */
+plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void *W,
+                              const void *const *A, const void *const *B, void *y,
+                              float *h_saved, void *workspace, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Backward (appendix C.2, cases 1-4; no gradient for W).
+ *   x, W, A, B as in the forward call;  dy DEVICE [T][d_out]
+ *   h_saved  DEVICE fp32 activation written by the forward call with the same inputs, or NULL
+ *            (then x_t A_k is recomputed)
+ *   dx       DEVICE [T][d_in], overwritten; NULL skips it
+ *   dA, dB   HOST arrays of n_adapters DEVICE fp32 pointers, dA[k] -> [d_in][r_k],
+ *            dB[k] -> [r_k][d_out]; overwritten (an adapter without tokens gets zeros; several
+ *            segments of one adapter are summed).  Both NULL skips the weight gradients.
+ */
+plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void *W,
+                              const void *const *A, const void *const *B, const void *dy,
+                              const float *h_saved, void *dx, float *const *dA,
+                              float *const *dB, void *workspace, size_t ws_bytes,
+                              void *hip_stream);
+
+/*
+ * Timing hook for benchmarks: when enabled (non-zero), every kernel of later calls is bracketed
+ * by HIP events on its own stream, and plora_last_kernel_ms returns the duration of the named
+ * kernel class in the most recent fwd or bwd call (after the caller has synchronised the
+ * stream).  Classes: 0 base GEMM forward, 1 dX GEMM, 2 shrink, 3 dH, 4 dB, 5 dA, 6 packing of
+ * the small operands, 7 W transpose.  Returns a negative value if nothing was recorded.
+ * Not thread-safe; meant for bench.py only.
+ */
+void plora_set_kernel_timing(int enabled);
+float plora_last_kernel_ms(int kernel_class);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLORA_H */

@@ -1,0 +1,359 @@
+// Host side of libplora: argument validation, the segment-packing metadata builder, workspace
+// layout and the launch sequences of the forward and backward calls.  No arithmetic of the layer
+// happens here; every step runs in the HIP kernels.
+#include "plora_internal.h"
+
+#include <cstring>
+#include <vector>
+
+namespace plora {
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int32_t pad_to(int32_t v, int32_t a) { return (v + a - 1) / a * a; }
+
+static plora_status validate(const plora_desc *d)
+{
+    if (!d) return PLORA_ERR_NULL;
+    if (d->dtype != PLORA_BF16 && d->dtype != PLORA_F32) return PLORA_ERR_UNSUPPORTED;
+    if (d->T < 0 || d->d_in <= 0 || d->d_out <= 0) return PLORA_ERR_SHAPE;
+    if (d->T > INT32_MAX || d->d_in > (1 << 24) || d->d_out > (1 << 24)) return PLORA_ERR_SHAPE;
+    if (d->dtype == PLORA_BF16 && (d->d_in % 8 != 0 || d->d_out % 8 != 0)) return PLORA_ERR_SHAPE;
+    if (d->n_seg < 0 || d->n_seg > PLORA_MAX_SEGMENTS) return PLORA_ERR_SEGMENTS;
+    if (d->n_adapters < 0 || d->n_adapters > PLORA_MAX_ADAPTERS) return PLORA_ERR_ADAPTER;
+    if (d->n_seg == 0) return d->T == 0 ? PLORA_OK : PLORA_ERR_SEGMENTS;
+    if (!d->seg_off || !d->seg_adapter) return PLORA_ERR_NULL;
+    if (d->n_adapters > 0 && (!d->rank || !d->scale)) return PLORA_ERR_NULL;
+    for (int32_t k = 0; k < d->n_adapters; ++k)
+        if (d->rank[k] < 1 || d->rank[k] > PLORA_MAX_RANK) return PLORA_ERR_RANK;
+    if (d->seg_off[0] != 0 || d->seg_off[d->n_seg] != d->T) return PLORA_ERR_SEGMENTS;
+    for (int32_t s = 0; s < d->n_seg; ++s) {
+        if (d->seg_off[s + 1] < d->seg_off[s]) return PLORA_ERR_SEGMENTS;
+        if (d->seg_adapter[s] < -1 || d->seg_adapter[s] >= d->n_adapters) return PLORA_ERR_ADAPTER;
+    }
+    return PLORA_OK;
+}
+
+// Host copy of the metadata blob plus the workspace layout derived from it.
+struct HostMeta {
+    MetaHeader hdr;
+    std::vector<SegInfo> seg;
+    std::vector<AdapterInfo> ad;
+    WorkspaceLayout ws;
+    size_t h_elems = 0, hb_elems = 0, zt_elems = 0, at_elems = 0, ap_elems = 0;
+};
+
+// The segment-packing metadata builder (host).  Pure integer work.
+static void build_meta(const plora_desc *d, HostMeta &m)
+{
+    m.hdr.T = d->T; m.hdr.D = d->d_in; m.hdr.K = d->d_out;
+    m.hdr.n_seg = d->n_seg; m.hdr.n_adapters = d->n_adapters; m.hdr.max_r16 = 0;
+    m.seg.resize(d->n_seg);
+    m.ad.resize(d->n_adapters);
+    int64_t at = 0, ap = 0;
+    for (int32_t k = 0; k < d->n_adapters; ++k) {
+        AdapterInfo &a = m.ad[k];
+        std::memset(&a, 0, sizeof(a));
+        a.r = d->rank[k];
+        a.rp = pad_to(a.r, kRankPadGemm);
+        a.r16 = pad_to(a.r, kRankPadMfma);
+        a.scale = d->scale[k];
+        a.at_off = at; at += (int64_t)a.r16 * d->d_in;
+        a.ap_off = ap; ap += (int64_t)a.rp * d->d_in;
+    }
+    int64_t h = 0, hb = 0, zt = 0;
+    int32_t blk = 0;
+    for (int32_t s = 0; s < d->n_seg; ++s) {
+        SegInfo &g = m.seg[s];
+        g.row0 = d->seg_off[s]; g.row1 = d->seg_off[s + 1];
+        g.adapter = d->seg_adapter[s];
+        const int32_t len = g.row1 - g.row0;
+        g.r = g.adapter >= 0 ? m.ad[g.adapter].r : 0;
+        g.rp = g.adapter >= 0 ? m.ad[g.adapter].rp : 0;
+        g.r16 = g.adapter >= 0 ? m.ad[g.adapter].r16 : 0;
+        g.lp = pad_to(len, kTokPad);
+        g.blk0 = blk;
+        g.h_off = h; g.hb_off = hb; g.zt_off = zt;
+        if (g.adapter >= 0) {
+            blk += (len + kSkinnyRows - 1) / kSkinnyRows;
+            if (len > 0 && g.r16 > m.hdr.max_r16) m.hdr.max_r16 = g.r16;
+            h += (int64_t)len * g.r;
+            hb += (int64_t)len * g.rp;
+            zt += (int64_t)g.r16 * g.lp;
+        }
+    }
+    m.hdr.n_blocks = blk;
+    m.h_elems = (size_t)h; m.hb_elems = (size_t)hb; m.zt_elems = (size_t)zt;
+    m.at_elems = (size_t)at; m.ap_elems = (size_t)ap;
+
+    WorkspaceLayout &w = m.ws;
+    size_t o = 0;
+    w.zero = o; o += kZeroBytes;
+    w.meta_bytes = sizeof(MetaHeader) + m.seg.size() * sizeof(SegInfo) + m.ad.size() * sizeof(AdapterInfo);
+    w.meta = o; o = align_up(o + w.meta_bytes, 256);
+    const bool bf = d->dtype == PLORA_BF16;
+    w.at = o;   o = align_up(o + (bf ? m.at_elems * 2 : 0), 256);
+    w.ap = o;   o = align_up(o + (bf ? m.ap_elems * 2 : 0), 256);
+    w.hb = o;   o = align_up(o + (bf ? m.hb_elems * 2 : 0), 256);
+    w.zt_h = o; o = align_up(o + (bf ? m.zt_elems * 2 : 0), 256);
+    w.zt_g = o; o = align_up(o + (bf ? m.zt_elems * 2 : 0), 256);
+    w.hf = o;   o = align_up(o + m.h_elems * 4, 256);
+    w.gf = o;   o = align_up(o + (bf ? 0 : m.h_elems * 4), 256);
+    w.wt = o;
+    w.total = o + 256;
+}
+
+// ---- bench-only kernel timing ------------------------------------------------------------------
+constexpr int kClasses = 8;
+static int g_timing = 0;
+static hipEvent_t g_ev[kClasses][2];
+static bool g_ev_made = false;
+static bool g_ev_used[kClasses];
+
+struct Bracket {
+    int cls; hipStream_t st; bool on;
+    Bracket(int c, hipStream_t s) : cls(c), st(s), on(g_timing != 0)
+    {
+        if (!on) return;
+        if (!g_ev_made) {
+            for (int i = 0; i < kClasses; ++i) { (void)hipEventCreate(&g_ev[i][0]); (void)hipEventCreate(&g_ev[i][1]); }
+            g_ev_made = true;
+        }
+        (void)hipEventRecord(g_ev[cls][0], st);
+    }
+    ~Bracket() { if (on) { (void)hipEventRecord(g_ev[cls][1], st); g_ev_used[cls] = true; } }
+};
+
+#define PL_TRY(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return PLORA_ERR_HIP; } while (0)
+
+static bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// Checks shared by forward and backward; fills the adapter pointer fields.
+static plora_status prepare(const plora_desc *d, const void *x, const void *W, const void *const *A,
+                            const void *const *B, void *workspace, size_t ws_bytes, HostMeta &m)
+{
+    plora_status st = validate(d);
+    if (st != PLORA_OK) return st;
+    if (!x && d->T > 0) return PLORA_ERR_NULL;
+    if (!W) return PLORA_ERR_NULL;
+    if (d->n_adapters > 0 && (!A || !B)) return PLORA_ERR_NULL;
+    for (int32_t k = 0; k < d->n_adapters; ++k) {
+        if (!A[k] || !B[k]) return PLORA_ERR_NULL;
+        if (misaligned(A[k]) || misaligned(B[k])) return PLORA_ERR_ALIGN;
+    }
+    if (misaligned(x) || misaligned(W)) return PLORA_ERR_ALIGN;
+    build_meta(d, m);
+    if (!workspace || ws_bytes < m.ws.total) return PLORA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
+    for (int32_t k = 0; k < d->n_adapters; ++k) { m.ad[k].A = A[k]; m.ad[k].B = B[k]; }
+    return PLORA_OK;
+}
+
+static hipError_t upload_meta(const HostMeta &m, char *ws, hipStream_t st, MetaView &mv)
+{
+    std::vector<char> blob(m.ws.meta_bytes);
+    char *p = blob.data();
+    std::memcpy(p, &m.hdr, sizeof(MetaHeader)); p += sizeof(MetaHeader);
+    if (!m.seg.empty()) std::memcpy(p, m.seg.data(), m.seg.size() * sizeof(SegInfo));
+    p += m.seg.size() * sizeof(SegInfo);
+    if (!m.ad.empty()) std::memcpy(p, m.ad.data(), m.ad.size() * sizeof(AdapterInfo));
+    char *dev = ws + m.ws.meta;
+    mv.hdr = reinterpret_cast<const MetaHeader *>(dev);
+    mv.seg = reinterpret_cast<const SegInfo *>(dev + sizeof(MetaHeader));
+    mv.ad = reinterpret_cast<const AdapterInfo *>(dev + sizeof(MetaHeader) + m.seg.size() * sizeof(SegInfo));
+    hipError_t e = clear_zero_page(ws + m.ws.zero, st);
+    if (e != hipSuccess) return e;
+    return upload_blob(dev, blob.data(), blob.size(), st);
+}
+
+}  // namespace plora
+
+using namespace plora;
+
+extern "C" {
+
+const char *plora_status_string(plora_status st)
+{
+    switch (st) {
+    case PLORA_OK: return "ok";
+    case PLORA_ERR_NULL: return "a required pointer is NULL";
+    case PLORA_ERR_SHAPE: return "bad T / d_in / d_out (bf16 needs multiples of 8)";
+    case PLORA_ERR_SEGMENTS: return "segment offsets must start at 0, end at T and not decrease";
+    case PLORA_ERR_ADAPTER: return "adapter id out of range or too many adapters";
+    case PLORA_ERR_RANK: return "rank outside [1, PLORA_MAX_RANK]";
+    case PLORA_ERR_ALIGN: return "device pointer not 16-byte aligned (workspace: 256)";
+    case PLORA_ERR_WORKSPACE: return "workspace missing or too small";
+    case PLORA_ERR_UNSUPPORTED: return "unsupported dtype";
+    case PLORA_ERR_HIP: return "HIP launch failed";
+    }
+    return "unknown status";
+}
+
+plora_status plora_validate(const plora_desc *desc) { return validate(desc); }
+
+size_t plora_h_elems(const plora_desc *desc)
+{
+    if (validate(desc) != PLORA_OK) return 0;
+    HostMeta m; build_meta(desc, m);
+    return m.h_elems;
+}
+
+size_t plora_workspace_bytes(const plora_desc *desc)
+{
+    if (validate(desc) != PLORA_OK) return 0;
+    HostMeta m; build_meta(desc, m);
+    return m.ws.total;
+}
+
+int64_t plora_build_metadata(const plora_desc *desc, int32_t block_rows, int64_t *h_off_out,
+                             int32_t *blocks_out, int64_t blocks_cap)
+{
+    if (validate(desc) != PLORA_OK || block_rows < 1) return -1;
+    HostMeta m; build_meta(desc, m);
+    if (h_off_out) {
+        for (int32_t s = 0; s < desc->n_seg; ++s) h_off_out[s] = m.seg[s].h_off;
+        h_off_out[desc->n_seg] = (int64_t)m.h_elems;
+    }
+    int64_t n = 0;
+    for (int32_t s = 0; s < desc->n_seg; ++s) {
+        const SegInfo &g = m.seg[s];
+        for (int32_t r0 = g.row0; r0 < g.row1; r0 += block_rows) {
+            if (blocks_out && n < blocks_cap) {
+                blocks_out[4 * n + 0] = r0;
+                blocks_out[4 * n + 1] = (g.row1 - r0 < block_rows) ? g.row1 - r0 : block_rows;
+                blocks_out[4 * n + 2] = s;
+                blocks_out[4 * n + 3] = g.adapter;
+            }
+            ++n;
+        }
+    }
+    return n;
+}
+
+void plora_set_kernel_timing(int enabled)
+{
+    g_timing = enabled;
+    for (int i = 0; i < kClasses; ++i) g_ev_used[i] = false;
+}
+
+float plora_last_kernel_ms(int cls)
+{
+    if (cls < 0 || cls >= kClasses || !g_ev_made || !g_ev_used[cls]) return -1.f;
+    float ms = -1.f;
+    if (hipEventElapsedTime(&ms, g_ev[cls][0], g_ev[cls][1]) != hipSuccess) return -1.f;
+    return ms;
+}
+
+plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void *W,
+                              const void *const *A, const void *const *B, void *y, float *h_saved,
+                              void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    HostMeta m;
+    plora_status ps = prepare(desc, x, W, A, B, workspace, ws_bytes, m);
+    if (ps != PLORA_OK) return ps;
+    if (!y && desc->T > 0) return PLORA_ERR_NULL;
+    if (misaligned(y) || misaligned(h_saved)) return PLORA_ERR_ALIGN;
+    if (desc->T == 0) return PLORA_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    for (int i = 0; i < kClasses; ++i) g_ev_used[i] = false;
+
+    MetaView mv;
+    PL_TRY(upload_meta(m, ws, st, mv));
+    float *hf = h_saved ? h_saved : reinterpret_cast<float *>(ws + m.ws.hf);
+    const bool lora = m.hdr.n_blocks > 0;
+
+    if (desc->dtype == PLORA_F32) {
+        const float *xf = static_cast<const float *>(x);
+        if (lora) { Bracket b(2, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hf, st)); }
+        { Bracket b(0, st);
+          PL_TRY(launch_f32_gemm(mv, m.hdr, true, xf, static_cast<const float *>(W), hf, static_cast<float *>(y), st)); }
+        return PLORA_OK;
+    }
+
+    void *at = ws + m.ws.at, *hb = ws + m.ws.hb;
+    if (lora) {
+        { Bracket b(6, st); PL_TRY(launch_pack_bf16(mv, m.hdr, at, nullptr, true, false, st)); }
+        { Bracket b(2, st);
+          PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, h_saved, hb, nullptr, false, st)); }
+    }
+    { Bracket b(0, st);
+      PL_TRY(launch_gemm_bf16(mv, m.hdr, true, x, W, hb, nullptr, ws + m.ws.zero, y, st)); }
+    return PLORA_OK;
+}
+
+plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void *W,
+                              const void *const *A, const void *const *B, const void *dy,
+                              const float *h_saved, void *dx, float *const *dA, float *const *dB,
+                              void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    HostMeta m;
+    plora_status ps = prepare(desc, x, W, A, B, workspace, ws_bytes, m);
+    if (ps != PLORA_OK) return ps;
+    if (!dy && desc->T > 0) return PLORA_ERR_NULL;
+    if (misaligned(dy) || misaligned(dx) || misaligned(h_saved)) return PLORA_ERR_ALIGN;
+    const bool want_w = (dA != nullptr) || (dB != nullptr);
+    if (want_w && desc->n_adapters > 0) {
+        if (!dA || !dB) return PLORA_ERR_NULL;
+        for (int32_t k = 0; k < desc->n_adapters; ++k) {
+            if (!dA[k] || !dB[k]) return PLORA_ERR_NULL;
+            if (misaligned(dA[k]) || misaligned(dB[k])) return PLORA_ERR_ALIGN;
+            m.ad[k].dA = dA[k]; m.ad[k].dB = dB[k];
+        }
+    }
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    char *ws = static_cast<char *>(workspace);
+    for (int i = 0; i < kClasses; ++i) g_ev_used[i] = false;
+    const bool lora = m.hdr.n_blocks > 0;
+    const bool any_w = want_w && desc->n_adapters > 0;
+    if (desc->T == 0 && !any_w) return PLORA_OK;
+
+    MetaView mv;
+    PL_TRY(upload_meta(m, ws, st, mv));
+
+    if (desc->dtype == PLORA_F32) {
+        const float *xf = static_cast<const float *>(x), *dyf = static_cast<const float *>(dy);
+        float *gf = reinterpret_cast<float *>(ws + m.ws.gf);
+        const float *hf = h_saved;
+        if (lora && any_w && !hf) {
+            Bracket b(2, st);
+            float *hw = reinterpret_cast<float *>(ws + m.ws.hf);
+            PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hw, st));
+            hf = hw;
+        }
+        if (lora) { Bracket b(3, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 1, dyf, desc->d_out, gf, st)); }
+        if (any_w) {
+            { Bracket b(4, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, false, dyf, desc->d_out, hf, st)); }
+            { Bracket b(5, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, true, xf, desc->d_in, gf, st)); }
+        }
+        if (dx && desc->T > 0) {
+            Bracket b(1, st);
+            PL_TRY(launch_f32_gemm(mv, m.hdr, false, dyf, static_cast<const float *>(W), gf, static_cast<float *>(dx), st));
+        }
+        return PLORA_OK;
+    }
+
+    void *at = ws + m.ws.at, *ap = ws + m.ws.ap, *gb = ws + m.ws.hb;
+    void *zt_h = ws + m.ws.zt_h, *zt_g = ws + m.ws.zt_g;
+    if (lora) {
+        const bool need_shrink = any_w && !h_saved;
+        { Bracket b(6, st); PL_TRY(launch_pack_bf16(mv, m.hdr, at, ap, need_shrink, dx != nullptr, st)); }
+        if (any_w) {
+            Bracket b(2, st);
+            if (h_saved) PL_TRY(launch_h_to_zt(mv, m.hdr, h_saved, zt_h, st));
+            else PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, nullptr, nullptr, zt_h, false, st));
+        }
+        { Bracket b(3, st);
+          PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, nullptr, gb, any_w ? zt_g : nullptr, true, st)); }
+    }
+    if (any_w) {
+        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + m.ws.zero, st)); }
+        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + m.ws.zero, st)); }
+    }
+    if (dx && desc->T > 0) {
+        Bracket b(1, st);
+        PL_TRY(launch_gemm_bf16(mv, m.hdr, false, dy, W, gb, ap, ws + m.ws.zero, dx, st));
+    }
+    return PLORA_OK;
+}
+
+}  // extern "C"

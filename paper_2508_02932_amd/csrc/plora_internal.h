@@ -1,0 +1,102 @@
+// Internal declarations shared by the host entry points and the HIP kernels of libplora.
+// Not part of the public interface (that is include/plora.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "plora.h"
+
+namespace plora {
+
+constexpr int kSkinnyRows = 64;    // token block of the shrink / dH kernel (never straddles a segment)
+constexpr int kRankPadGemm = 64;   // ranks are padded to one K-step of the GEMM in the bf16 side buffers
+constexpr int kRankPadMfma = 16;   // ranks are padded to one MFMA block in the skinny kernels
+constexpr int kTokPad = 64;        // segment lengths are padded to this in the transposed side buffers
+constexpr int kZeroBytes = 1024;   // zero page at the head of the workspace
+
+// One entry per segment of the call (empty and base-only segments included).
+struct SegInfo {
+    int32_t row0, row1;   // token rows [row0, row1)
+    int32_t adapter;      // -1: base weight only
+    int32_t r;            // rank of the adapter (0 if none)
+    int32_t rp;           // rank padded to kRankPadGemm: row pitch of the bf16 side buffer (0 if none)
+    int32_t r16;          // rank padded to kRankPadMfma
+    int32_t blk0;         // index of this segment's first token block (blocks of kSkinnyRows rows)
+    int32_t lp;           // segment length padded to kTokPad: row pitch of the transposed side buffers
+    int64_t h_off;        // element offset of the segment in the fp32 activation  [len][r]
+    int64_t hb_off;       // element offset in the bf16 side buffer                [len][rp]
+    int64_t zt_off;       // element offset in the transposed bf16 side buffers    [r16][lp]
+};
+
+// One entry per adapter.
+struct AdapterInfo {
+    const void *A;        // [d_in][r]
+    const void *B;        // [r][d_out]
+    float *dA;            // [d_in][r]   (backward only)
+    float *dB;            // [r][d_out]  (backward only)
+    int32_t r, rp, r16;
+    float scale;
+    int64_t at_off;       // element offset of A^T  [r16][d_in]  in the packed-A^T buffer
+    int64_t ap_off;       // element offset of A    [d_in][rp]   in the padded-A buffer
+};
+
+struct MetaHeader {
+    int64_t T, D, K;
+    int32_t n_seg, n_adapters;
+    int32_t n_blocks;     // token blocks of kSkinnyRows rows over all segments
+    int32_t max_r16;      // largest rank (padded to 16) among segments with tokens
+};
+
+// Device view of the metadata blob (all pointers into the workspace).
+struct MetaView {
+    const MetaHeader *hdr;
+    const SegInfo *seg;
+    const AdapterInfo *ad;
+};
+
+// Byte offsets of the workspace regions, each 256-byte aligned.
+struct WorkspaceLayout {
+    size_t zero, meta, at, ap, hb, zt_h, zt_g, hf, gf, wt, total;
+    size_t meta_bytes;
+};
+
+struct KernelTimer;   // bench-only event bracketing, see plora_api.hip
+
+// ---- launch wrappers implemented in the kernel files; all enqueue on `st` and return the HIP status ----
+
+hipError_t upload_blob(void *dst_dev, const void *src_host, size_t bytes, hipStream_t st);
+hipError_t clear_zero_page(void *zero_dev, hipStream_t st);
+
+// bf16 path -------------------------------------------------------------------------------------
+// Packs A_k^T (zero rows beyond r) and/or A_k padded to rp columns.
+hipError_t launch_pack_bf16(const MetaView &mv, const MetaHeader &h, void *at, void *ap, bool want_at,
+                            bool want_ap, hipStream_t st);
+// Skinny product over token blocks: acc[t][j] = sum_c S[t][c] * Bm_k[j][c]  (c < C).
+//   mode 0 (shrink): S = x (C = d_in), Bm_k = packed A_k^T;  mode 1 (dH): S = dy (C = d_out), Bm_k = B_k.
+//   Writes (each optional): hf fp32 [len][r] unscaled; hb bf16 [len][rp] = mult*acc; zt bf16 [r16][lp]
+//   transposed, = (scale_t ? mult : 1) * acc, where mult = scale_k.
+hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode, const void *S, int64_t C,
+                              const void *at, float *hf, void *hb, void *zt, bool zt_scaled, hipStream_t st);
+// Transposed bf16 copy of a saved fp32 activation: zt[j][t] = bf16(h[t][j]).
+hipError_t launch_h_to_zt(const MetaView &mv, const MetaHeader &h, const float *hf, void *zt, hipStream_t st);
+// C[T][N] = S[T][Kd] * Wop + side[T][rp] * ext_k, rounded to bf16.
+//   forward : S = x,  Wop = W [Kd=d_in][N=d_out] (contraction index is the row index), ext_k = B_k [r][N]
+//   backward: S = dy, Wop = W [N=d_in][Kd=d_out] (contraction index is contiguous),    ext_k = padded A_k [N][rp]
+hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool forward, const void *S, const void *W,
+                            const void *side, const void *ap, const void *zero, void *C, hipStream_t st);
+// Token contraction: out_k = mult * sum_t S[t][c] * zt[j][t] over all segments of adapter k.
+//   want_dA: S = x, out = dA_k[c][j], mult = 1;  else S = dy, out = dB_k[j][c], mult = scale_k.
+hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool want_dA, const void *S,
+                                   int64_t C, const void *zt, const void *zero, hipStream_t st);
+
+// fp32 path (fp64 accumulation) ---------------------------------------------------------------------
+hipError_t launch_f32_lowrank(const MetaView &mv, const MetaHeader &h, int mode, const float *S, int64_t C,
+                              float *out, hipStream_t st);
+hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward, const float *S, const float *W,
+                           const float *side, float *C, hipStream_t st);
+hipError_t launch_f32_wgrad(const MetaView &mv, const MetaHeader &h, bool want_dA, const float *S, int64_t C,
+                            const float *side, hipStream_t st);
+
+}  // namespace plora

@@ -1,0 +1,139 @@
+// Small helper kernels of libplora: metadata upload through kernel arguments, zero page, packing
+// of the adapter matrices into MFMA-friendly bf16 buffers, transposed copy of a saved activation.
+#include "plora_internal.h"
+
+#include <cstring>
+
+namespace plora {
+
+// ---- metadata upload -------------------------------------------------------------------------
+// The blob travels as a by-value kernel argument, so the host copy is consumed at launch time
+// and no pinned staging buffer or host-to-device copy is needed (the call stays capturable).
+constexpr int kChunkWords = 896;   // 3584 bytes per launch, below the 4 KB kernel-argument limit
+struct BlobChunk { uint32_t w[kChunkWords]; };
+
+__global__ void __launch_bounds__(256) k_upload(BlobChunk c, uint32_t *dst, int n_words)
+{
+    for (int i = threadIdx.x; i < n_words; i += 256) dst[i] = c.w[i];
+}
+
+hipError_t upload_blob(void *dst_dev, const void *src_host, size_t bytes, hipStream_t st)
+{
+    const size_t words = (bytes + 3) / 4;
+    const char *src = static_cast<const char *>(src_host);
+    for (size_t w0 = 0; w0 < words; w0 += kChunkWords) {
+        BlobChunk c;
+        const size_t nw = (words - w0 < (size_t)kChunkWords) ? words - w0 : (size_t)kChunkWords;
+        const size_t b0 = w0 * 4;
+        const size_t nb = (bytes - b0 < nw * 4) ? bytes - b0 : nw * 4;
+        std::memset(&c, 0, sizeof(c));
+        std::memcpy(c.w, src + b0, nb);
+        hipLaunchKernelGGL(k_upload, dim3(1), dim3(256), 0, st, c, static_cast<uint32_t *>(dst_dev) + w0, (int)nw);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+__global__ void __launch_bounds__(256) k_zero_page(uint32_t *p)
+{
+    p[threadIdx.x] = 0u;   // kZeroBytes = 256 * 4
+}
+
+hipError_t clear_zero_page(void *zero_dev, hipStream_t st)
+{
+    static_assert(kZeroBytes == 1024, "zero page is written by one 256-thread block");
+    hipLaunchKernelGGL(k_zero_page, dim3(1), dim3(256), 0, st, static_cast<uint32_t *>(zero_dev));
+    return hipGetLastError();
+}
+
+// ---- packing of A_k ------------------------------------------------------------------------------
+// at: A_k^T as [r16][D] (rows j >= r are zero) - the "row = output column, contraction contiguous"
+//     operand of the shrink kernel.
+// ap: A_k as [D][rp] with columns j >= r zero - the low-rank K-extension operand of the dX GEMM.
+// One block handles 64 rows i of one adapter; the tile goes through LDS so that both the reads of
+// A_k (contiguous in j) and the writes of A_k^T (contiguous in i) are coalesced.
+__global__ void __launch_bounds__(256) k_pack_a(MetaView mv, uint16_t *at, uint16_t *ap, int want_at, int want_ap)
+{
+    __shared__ uint16_t tile[64][PLORA_MAX_RANK + 2];
+    const int k = blockIdx.y;
+    const AdapterInfo a = mv.ad[k];
+    const int64_t D = mv.hdr->D;
+    const int64_t i0 = (int64_t)blockIdx.x * 64;
+    const uint16_t *A = static_cast<const uint16_t *>(a.A);
+    const int r = a.r;
+    const int rows = (int)((D - i0 < 64) ? D - i0 : 64);
+    for (int e = threadIdx.x; e < rows * r; e += 256) {
+        const int ii = e / r, j = e % r;
+        tile[ii][j] = A[(i0 + ii) * r + j];
+    }
+    __syncthreads();
+    if (want_at) {
+        uint16_t *dst = at + a.at_off;
+        for (int e = threadIdx.x; e < a.r16 * 64; e += 256) {
+            const int j = e / 64, ii = e % 64;
+            if (ii < rows) dst[(int64_t)j * D + i0 + ii] = (j < r) ? tile[ii][j] : (uint16_t)0;
+        }
+    }
+    if (want_ap) {
+        uint16_t *dst = ap + a.ap_off;
+        for (int e = threadIdx.x; e < 64 * a.rp; e += 256) {
+            const int ii = e / a.rp, j = e % a.rp;
+            if (ii < rows) dst[(i0 + ii) * a.rp + j] = (j < r) ? tile[ii][j] : (uint16_t)0;
+        }
+    }
+}
+
+hipError_t launch_pack_bf16(const MetaView &mv, const MetaHeader &h, void *at, void *ap, bool want_at,
+                            bool want_ap, hipStream_t st)
+{
+    if (h.n_adapters == 0 || (!want_at && !want_ap)) return hipSuccess;
+    dim3 grid((unsigned)((h.D + 63) / 64), (unsigned)h.n_adapters);
+    hipLaunchKernelGGL(k_pack_a, grid, dim3(256), 0, st, mv, static_cast<uint16_t *>(at),
+                       static_cast<uint16_t *>(ap), want_at ? 1 : 0, want_ap ? 1 : 0);
+    return hipGetLastError();
+}
+
+// ---- transposed bf16 copy of a saved fp32 activation ------------------------------------------------
+__device__ inline uint16_t f32_to_bf16_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// One block per token block of kSkinnyRows rows: zt[j][t] = bf16(h[t][j]); rows j >= r and the
+// padding columns of the block are written as zero.
+__global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, uint16_t *zt)
+{
+    __shared__ float tile[kSkinnyRows][PLORA_MAX_RANK + 1];
+    const int blk = blockIdx.x;
+    const int n_seg = mv.hdr->n_seg;
+    int s = 0;
+    for (int q = 0; q < n_seg; ++q) {
+        const SegInfo g = mv.seg[q];
+        if (g.adapter >= 0 && g.row1 > g.row0 && blk >= g.blk0) s = q;
+    }
+    const SegInfo g = mv.seg[s];
+    const int t0 = (blk - g.blk0) * kSkinnyRows;        // first token of the block inside the segment
+    const int len = g.row1 - g.row0;
+    const int nt = (len - t0 < kSkinnyRows) ? len - t0 : kSkinnyRows;
+    const float *src = hf + g.h_off + (int64_t)t0 * g.r;
+    for (int e = threadIdx.x; e < nt * g.r; e += 256) tile[e / g.r][e % g.r] = src[e];
+    __syncthreads();
+    uint16_t *dst = zt + g.zt_off;
+    for (int e = threadIdx.x; e < g.r16 * kSkinnyRows; e += 256) {
+        const int j = e / kSkinnyRows, tt = e % kSkinnyRows;
+        if (t0 + tt < g.lp)
+            dst[(int64_t)j * g.lp + t0 + tt] = (j < g.r && tt < nt) ? f32_to_bf16_rne(tile[tt][j]) : (uint16_t)0;
+    }
+}
+
+hipError_t launch_h_to_zt(const MetaView &mv, const MetaHeader &h, const float *hf, void *zt, hipStream_t st)
+{
+    if (h.n_blocks == 0) return hipSuccess;
+    hipLaunchKernelGGL(k_h_to_zt, dim3((unsigned)h.n_blocks), dim3(256), 0, st, mv, hf, static_cast<uint16_t *>(zt));
+    return hipGetLastError();
+}
+
+}  // namespace plora

@@ -1,0 +1,183 @@
+"""ctypes binding of libplora (include/plora.h).  Argument marshalling only.
+
+Every function here has the name and the meaning of the C entry point it calls; torch tensors
+are used as owners of device memory and as the source of the HIP stream, nothing is computed in
+Python.  The library must have been built (``python -m paper_2508_02932_amd.build`` or
+``__graft_entry__.build()``); there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libplora.so")
+
+PLORA_BF16, PLORA_F32 = 0, 1
+PLORA_OK = 0
+PLORA_MAX_RANK, PLORA_MAX_ADAPTERS, PLORA_MAX_SEGMENTS = 128, 256, 1024
+KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "pack": 6}
+
+EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_workspace_bytes",
+           "plora_build_metadata", "plora_linear_fwd", "plora_linear_bwd",
+           "plora_set_kernel_timing", "plora_last_kernel_ms"]
+
+
+class PloraError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"plora status {code}: {text}")
+        self.code = code
+
+
+class plora_desc(C.Structure):
+    _fields_ = [("T", C.c_int64), ("d_in", C.c_int64), ("d_out", C.c_int64),
+                ("n_seg", C.c_int32), ("n_adapters", C.c_int32),
+                ("seg_off", C.c_void_p), ("seg_adapter", C.c_void_p),
+                ("rank", C.c_void_p), ("scale", C.c_void_p), ("dtype", C.c_int32)]
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared library; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it first (python -m paper_2508_02932_amd.build)")
+        L = C.CDLL(LIB_PATH)
+        L.plora_status_string.restype = C.c_char_p
+        L.plora_status_string.argtypes = [C.c_int]
+        L.plora_validate.restype = C.c_int
+        L.plora_validate.argtypes = [C.POINTER(plora_desc)]
+        L.plora_h_elems.restype = C.c_size_t
+        L.plora_h_elems.argtypes = [C.POINTER(plora_desc)]
+        L.plora_workspace_bytes.restype = C.c_size_t
+        L.plora_workspace_bytes.argtypes = [C.POINTER(plora_desc)]
+        L.plora_build_metadata.restype = C.c_int64
+        L.plora_build_metadata.argtypes = [C.POINTER(plora_desc), C.c_int32, C.c_void_p, C.c_void_p, C.c_int64]
+        L.plora_linear_fwd.restype = C.c_int
+        L.plora_linear_fwd.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
+        L.plora_linear_bwd.restype = C.c_int
+        L.plora_linear_bwd.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
+        L.plora_set_kernel_timing.restype = None
+        L.plora_set_kernel_timing.argtypes = [C.c_int]
+        L.plora_last_kernel_ms.restype = C.c_float
+        L.plora_last_kernel_ms.argtypes = [C.c_int]
+        _lib = L
+    return _lib
+
+
+@dataclass
+class Desc:
+    """Host-side description of one call; keeps the numpy arrays the C struct points at alive."""
+    T: int
+    d_in: int
+    d_out: int
+    seg_off: np.ndarray
+    seg_adapter: np.ndarray
+    rank: np.ndarray
+    scale: np.ndarray
+    dtype: int
+
+    def __post_init__(self):
+        self.seg_off = np.ascontiguousarray(self.seg_off, dtype=np.int32)
+        self.seg_adapter = np.ascontiguousarray(self.seg_adapter, dtype=np.int32)
+        self.rank = np.ascontiguousarray(self.rank, dtype=np.int32)
+        self.scale = np.ascontiguousarray(self.scale, dtype=np.float32)
+        self.c = plora_desc(self.T, self.d_in, self.d_out, len(self.seg_adapter), len(self.rank),
+                            self.seg_off.ctypes.data, self.seg_adapter.ctypes.data,
+                            self.rank.ctypes.data if len(self.rank) else None,
+                            self.scale.ctypes.data if len(self.scale) else None, self.dtype)
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def _check(code: int):
+    if code != PLORA_OK:
+        raise PloraError(code, plora_status_string(code))
+
+
+def plora_status_string(code: int) -> str:
+    return lib().plora_status_string(int(code)).decode()
+
+
+def plora_validate(d: Desc) -> int:
+    return int(lib().plora_validate(d.ref))
+
+
+def plora_h_elems(d: Desc) -> int:
+    return int(lib().plora_h_elems(d.ref))
+
+
+def plora_workspace_bytes(d: Desc) -> int:
+    return int(lib().plora_workspace_bytes(d.ref))
+
+
+def plora_build_metadata(d: Desc, block_rows: int):
+    """(h_off[n_seg+1] int64, blocks[n, 4] int32) or raises on an invalid description."""
+    n = int(lib().plora_build_metadata(d.ref, block_rows, None, None, 0))
+    if n < 0:
+        raise PloraError(-1, "invalid description")
+    h_off = np.zeros(len(d.seg_adapter) + 1, dtype=np.int64)
+    blocks = np.zeros((max(n, 1), 4), dtype=np.int32)
+    n2 = int(lib().plora_build_metadata(d.ref, block_rows, h_off.ctypes.data, blocks.ctypes.data, n))
+    assert n2 == n
+    return h_off, blocks[:n]
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else int(t.data_ptr())
+
+
+def _ptr_table(tensors: Optional[Sequence]):
+    if tensors is None:
+        return None, None
+    arr = (C.c_void_p * max(len(tensors), 1))(*[int(t.data_ptr()) for t in tensors])
+    return arr, C.cast(arr, C.c_void_p)
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) or None
+
+
+def plora_linear_fwd(d: Desc, x, W, A: Sequence, B: Sequence, y, h_saved, workspace, stream=None) -> None:
+    """Enqueues the forward call; tensors are torch device tensors (h_saved may be None)."""
+    ka, pa = _ptr_table(A)
+    kb, pb = _ptr_table(B)
+    code = lib().plora_linear_fwd(d.ref, _ptr(x), _ptr(W), pa, pb, _ptr(y), _ptr(h_saved),
+                                  _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                  _stream(stream))
+    _check(code)
+
+
+def plora_linear_bwd(d: Desc, x, W, A: Sequence, B: Sequence, dy, h_saved, dx, dA: Optional[Sequence],
+                     dB: Optional[Sequence], workspace, stream=None) -> None:
+    """Enqueues the backward call; dx may be None, dA and dB may both be None."""
+    ka, pa = _ptr_table(A)
+    kb, pb = _ptr_table(B)
+    kda, pda = _ptr_table(dA)
+    kdb, pdb = _ptr_table(dB)
+    code = lib().plora_linear_bwd(d.ref, _ptr(x), _ptr(W), pa, pb, _ptr(dy), _ptr(h_saved), _ptr(dx),
+                                  pda, pdb, _ptr(workspace),
+                                  workspace.numel() * workspace.element_size(), _stream(stream))
+    _check(code)
+
+
+def plora_set_kernel_timing(enabled: bool) -> None:
+    lib().plora_set_kernel_timing(1 if enabled else 0)
+
+
+def plora_last_kernel_ms(kernel_class) -> float:
+    if isinstance(kernel_class, str):
+        kernel_class = KERNEL_CLASSES[kernel_class]
+    return float(lib().plora_last_kernel_ms(int(kernel_class)))

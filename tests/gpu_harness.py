@@ -1,0 +1,94 @@
+"""Runs the HIP library on a workload and brings the results back as numpy arrays.
+
+Only marshalling: torch owns the device memory, every step of the layer runs in libplora.
+Outputs are pre-filled with NaN so that an element the kernels fail to write shows up.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import List, Optional
+
+import numpy as np
+import torch
+
+from paper_2508_02932_amd import plora
+from paper_2508_02932_amd import workloads as wl
+
+
+def desc_of(lin: wl.Linear) -> plora.Desc:
+    lay = lin.layout
+    return plora.Desc(lay.T, lin.D, lin.K, lay.seg_off, lay.seg_adapter, lay.rank, lay.scale,
+                      plora.PLORA_BF16 if lin.dtype == "bf16" else plora.PLORA_F32)
+
+
+def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
+    t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    return t.to(torch.bfloat16) if dtype == "bf16" else t
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    return t.detach().float().cpu().numpy()
+
+
+@dataclass
+class DeviceProblem:
+    lin: wl.Linear
+    desc: plora.Desc
+    x: torch.Tensor
+    W: torch.Tensor
+    A: List[torch.Tensor]
+    B: List[torch.Tensor]
+    dy: Optional[torch.Tensor]
+    ws: torch.Tensor
+    h: torch.Tensor
+    y: torch.Tensor
+    dx: torch.Tensor
+    dA: List[torch.Tensor]
+    dB: List[torch.Tensor]
+
+
+def upload(lin: wl.Linear, t: wl.Tensors) -> DeviceProblem:
+    d = desc_of(lin)
+    tdt = torch.bfloat16 if lin.dtype == "bf16" else torch.float32
+    ws_bytes = plora.plora_workspace_bytes(d)
+    assert ws_bytes > 0
+    dev = "cuda"
+    nan = float("nan")
+    T, D, K = lin.layout.T, lin.D, lin.K
+    return DeviceProblem(
+        lin, d, to_dev(t.x, lin.dtype), to_dev(t.W, lin.dtype),
+        [to_dev(a, lin.dtype) for a in t.A], [to_dev(b, lin.dtype) for b in t.B],
+        None if t.dy is None else to_dev(t.dy, lin.dtype),
+        torch.empty(ws_bytes, dtype=torch.uint8, device=dev),
+        torch.full((max(plora.plora_h_elems(d), 1),), nan, dtype=torch.float32, device=dev),
+        torch.full((T, K), nan, dtype=tdt, device=dev),
+        torch.full((T, D), nan, dtype=tdt, device=dev),
+        [torch.full((D, int(r)), nan, dtype=torch.float32, device=dev) for r in lin.layout.rank],
+        [torch.full((int(r), K), nan, dtype=torch.float32, device=dev) for r in lin.layout.rank])
+
+
+def forward(p: DeviceProblem, save_h: bool = True):
+    plora.plora_linear_fwd(p.desc, p.x, p.W, p.A, p.B, p.y, p.h if save_h else None, p.ws)
+
+
+def backward(p: DeviceProblem, use_saved_h: bool = True, want_dx: bool = True, want_w: bool = True):
+    plora.plora_linear_bwd(p.desc, p.x, p.W, p.A, p.B, p.dy, p.h if use_saved_h else None,
+                           p.dx if want_dx else None, p.dA if want_w else None,
+                           p.dB if want_w else None, p.ws)
+
+
+def ragged_h_to_rows(lin: wl.Linear, h_flat: np.ndarray) -> np.ndarray:
+    """Ragged saved activation -> [T, r_max] with zeros beyond each row's rank (the oracle's layout)."""
+    lay = lin.layout
+    pitch = int(lay.rank.max()) if lay.n_adapters else 1
+    out = np.zeros((lay.T, pitch), dtype=np.float64)
+    off = 0
+    for s in range(lay.n_seg):
+        k = int(lay.seg_adapter[s])
+        lo, hi = int(lay.seg_off[s]), int(lay.seg_off[s + 1])
+        if k < 0:
+            continue
+        r = int(lay.rank[k])
+        out[lo:hi, :r] = h_flat[off:off + (hi - lo) * r].reshape(hi - lo, r)
+        off += (hi - lo) * r
+    return out

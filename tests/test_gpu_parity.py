@@ -1,0 +1,205 @@
+"""GPU parity: the HIP library against the fp64 CPU oracle, element by element, on the same seeded
+inputs.  Sizes here are ones the oracle finishes in seconds, yet they span several tiles of every
+kernel and have ragged tails.  Tolerances (scaled error, see util.scaled_err): 2e-2 for bf16 I/O
+with fp32 accumulation, 1e-5 for fp32 I/O; segment indexing is implicit in every comparison (a
+wrong row or adapter is an O(1) error)."""
+import sys
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2508_02932_amd import workloads as wl
+from util import make_problem, scaled_err
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"bf16": 2e-2, "f32": 1e-5}
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def run_and_compare(lin, t=None, impl=None, save_h=True, check_h=True):
+    import torch
+    import gpu_harness as gh
+    t = t or lin.tensors()
+    impl = impl or oracle.loops
+    tol = TOL[lin.dtype]
+    say(f"[case] {lin.name} dtype={lin.dtype} T={lin.layout.T} D={lin.D} K={lin.K} "
+        f"ranks={lin.layout.rank.tolist()} segs={np.diff(lin.layout.seg_off).tolist()} "
+        f"adapters={lin.layout.seg_adapter.tolist()} save_h={save_h}")
+    p = make_problem(oracle, lin, t)
+    y_o, h_o = impl.forward(p)
+    dx_o, g_o, dA_o, dB_o = impl.backward(p, t.dy)
+
+    dp = gh.upload(lin, t)
+    say("  forward")
+    gh.forward(dp, save_h=save_h)
+    torch.cuda.synchronize()
+    say("  backward")
+    gh.backward(dp, use_saved_h=save_h)
+    torch.cuda.synchronize()
+    y = gh.to_np(dp.y)
+    dx = gh.to_np(dp.dx)
+    errs = {"y": scaled_err(y, y_o), "dx": scaled_err(dx, dx_o)}
+    if save_h and check_h and lin.layout.sum_Lr() > 0:
+        h = gh.ragged_h_to_rows(lin, gh.to_np(dp.h)[:lin.layout.sum_Lr()])
+        errs["h"] = scaled_err(h, h_o)
+    for k in range(lin.layout.n_adapters):
+        errs[f"dA{k}"] = scaled_err(gh.to_np(dp.dA[k]), dA_o[k])
+        errs[f"dB{k}"] = scaled_err(gh.to_np(dp.dB[k]), dB_o[k])
+    say("  errors " + " ".join(f"{k}={v:.2e}" for k, v in errs.items()))
+    for k, v in errs.items():
+        assert np.isfinite(v) and v <= tol, (lin.name, k, v, tol)
+    return dp, errs
+
+
+def test_config1_fp32_full():
+    run_and_compare(wl.config(1)[0])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_ragged_small(dtype):
+    """Repeated adapter, base-only segment, empty segment, segment lengths that are no multiple of
+    any tile, D and K that are multiples of 8 only."""
+    lin = wl.small(f"ragged_{dtype}", dtype, 328, 264, lengths=[130, 0, 257, 64, 249, 1],
+                   seg_adapter=[1, 0, 2, -1, 1, 0], ranks=[8, 24, 72], scales=[2.0, 0.5, 1.25], seed=41)
+    run_and_compare(lin)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_recompute_h_path(dtype):
+    """Backward without the saved activation recomputes x A_k."""
+    lin = wl.small(f"recompute_{dtype}", dtype, 256, 192, lengths=[100, 300], seg_adapter=[0, 1],
+                   ranks=[16, 40], scales=[2.0, 2.0], seed=43)
+    run_and_compare(lin, save_h=False)
+
+
+def test_bf16_several_tiles():
+    """More than one 256x256 GEMM tile in both directions, tiles that straddle three segments,
+    rank 1 and the maximum rank 128, odd rank."""
+    lin = wl.small("tiles_bf16", "bf16", 576, 520, lengths=[200, 90, 310, 7, 180],
+                   seg_adapter=[0, 1, 2, 3, 0], ranks=[128, 1, 33, 64], scales=[2.0, 4.0, 0.25, 1.0], seed=47)
+    run_and_compare(lin)
+
+
+def test_bf16_pure_lora_delta():
+    """W = 0 isolates the low-rank path, so its error is measured against its own magnitude."""
+    lin = wl.small("w0_bf16", "bf16", 512, 512, lengths=[300, 212], seg_adapter=[1, 0], ranks=[16, 64],
+                   scales=[2.0, 2.0], seed=53)
+    t = lin.tensors()
+    t.W = np.zeros_like(t.W)
+    run_and_compare(lin, t)
+
+
+def test_bf16_zero_B():
+    lin = wl.small("b0_bf16", "bf16", 256, 256, lengths=[128, 128], seg_adapter=[0, 1], ranks=[8, 32],
+                   scales=[2.0, 2.0], seed=59)
+    t = lin.tensors()
+    t.B = [np.zeros_like(b) for b in t.B]
+    dp, _ = run_and_compare(lin, t)
+    import gpu_harness as gh
+    for k in range(2):
+        assert not gh.to_np(dp.dA[k]).any()      # exactly zero, as in the oracle
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_edge_cases(dtype):
+    import torch
+    import gpu_harness as gh
+    # adapter without tokens, all-base batch, single token
+    lin = wl.small(f"edge_{dtype}", dtype, 64, 72, lengths=[1, 0, 5], seg_adapter=[0, 1, -1], ranks=[4, 16],
+                   scales=[1.0, 3.0], seed=61)
+    dp, _ = run_and_compare(lin)
+    assert not gh.to_np(dp.dA[1]).any() and not gh.to_np(dp.dB[1]).any()
+    lin = wl.small(f"base_only_{dtype}", dtype, 64, 64, lengths=[70], seg_adapter=[-1], ranks=[8], scales=[1.0], seed=67)
+    run_and_compare(lin)
+    # empty batch: forward is a no-op, backward writes zero weight gradients
+    lin = wl.small(f"empty_{dtype}", dtype, 64, 64, lengths=[0], seg_adapter=[0], ranks=[8], scales=[1.0], seed=71)
+    say(f"[case] {lin.name}")
+    t = lin.tensors()
+    dp = gh.upload(lin, t)
+    gh.forward(dp)
+    gh.backward(dp)
+    torch.cuda.synchronize()
+    assert not gh.to_np(dp.dA[0]).any() and not gh.to_np(dp.dB[0]).any()
+
+
+def test_skip_outputs():
+    """dx = NULL and dA = dB = NULL are honoured (the skipped outputs keep their NaN fill)."""
+    import torch
+    import gpu_harness as gh
+    lin = wl.small("skip_bf16", "bf16", 128, 128, lengths=[96, 64], seg_adapter=[0, 1], ranks=[8, 16],
+                   scales=[2.0, 2.0], seed=73)
+    t = lin.tensors()
+    p = make_problem(oracle, lin, t)
+    dx_o, _, dA_o, dB_o = oracle.loops.backward(p, t.dy)
+    dp = gh.upload(lin, t)
+    say("[case] skip dx")
+    gh.forward(dp)
+    gh.backward(dp, want_dx=False)
+    torch.cuda.synchronize()
+    assert np.isnan(gh.to_np(dp.dx)).all()
+    assert scaled_err(gh.to_np(dp.dA[1]), dA_o[1]) < 2e-2
+    dp = gh.upload(lin, t)
+    say("[case] skip dA/dB")
+    gh.forward(dp)
+    gh.backward(dp, want_w=False)
+    torch.cuda.synchronize()
+    assert np.isnan(gh.to_np(dp.dA[0])).all() and np.isnan(gh.to_np(dp.dB[1])).all()
+    assert scaled_err(gh.to_np(dp.dx), dx_o) < 2e-2
+
+
+def test_bf16_exact_integers():
+    """Small-integer inputs: every product and partial sum is exact in bf16 x bf16 -> fp32, and the
+    bf16 intermediates (h, g) are integers below 256, so the GPU must match the oracle with zero
+    error after the final rounding."""
+    import torch
+    import gpu_harness as gh
+    rng = np.random.default_rng(5)
+    D = K = 256
+    lens = [70, 130, 56]
+    ranks = [4, 8]
+
+    def sparse(shape):
+        return (rng.integers(-1, 2, size=shape) * (rng.random(shape) < 0.125)).astype(np.float32)
+
+    lin = wl.small("exact_bf16", "bf16", D, K, lengths=lens, seg_adapter=[0, 1, 0], ranks=ranks, scales=[1.0, 2.0])
+    T = sum(lens)
+    t = wl.Tensors(sparse((T, D)), sparse((D, K)), [sparse((D, r)) for r in ranks],
+                   [sparse((r, K)) for r in ranks], sparse((T, K)))
+    p = make_problem(oracle, lin, t)
+    y_o, _ = oracle.loops.forward(p)
+    dx_o, _, dA_o, dB_o = oracle.loops.backward(p, t.dy)
+    say("[case] exact integers")
+    dp = gh.upload(lin, t)
+    gh.forward(dp)
+    gh.backward(dp)
+    torch.cuda.synchronize()
+    assert np.array_equal(gh.to_np(dp.y), wl.round_to_bf16(y_o.astype(np.float32)))
+    assert np.array_equal(gh.to_np(dp.dx), wl.round_to_bf16(dx_o.astype(np.float32)))
+    for k in range(2):
+        assert np.array_equal(gh.to_np(dp.dA[k]), dA_o[k].astype(np.float32))
+        assert np.array_equal(gh.to_np(dp.dB[k]), dB_o[k].astype(np.float32))
+
+
+def test_run_twice_bitwise_identical():
+    """No atomics and a fixed summation order: two runs give the same bits."""
+    import torch
+    import gpu_harness as gh
+    lin = wl.small("twice_bf16", "bf16", 512, 384, lengths=[333, 190, 77], seg_adapter=[0, 1, 0], ranks=[24, 64],
+                   scales=[2.0, 2.0], seed=79)
+    t = lin.tensors()
+    outs = []
+    for rep in range(2):
+        say(f"[case] run twice, run {rep}")
+        dp = gh.upload(lin, t)
+        gh.forward(dp)
+        gh.backward(dp)
+        torch.cuda.synchronize()
+        outs.append([gh.to_np(dp.y), gh.to_np(dp.dx)] + [gh.to_np(a) for a in dp.dA] + [gh.to_np(b) for b in dp.dB])
+    for a, b in zip(*outs):
+        assert np.array_equal(a, b)

@@ -1,0 +1,133 @@
+"""Host-side checks that need no GPU: the library loads and exports what include/plora.h declares,
+argument validation returns the documented codes before anything could be launched, and the
+segment-packing metadata equals a brute-force construction bit for bit."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2508_02932_amd import plora
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "plora.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(plora_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert "plora_linear_fwd" in names and "plora_linear_bwd" in names
+    L = plora.lib()
+    for n in names:
+        assert hasattr(L, n), f"{n} declared in plora.h but not exported"
+    assert sorted(plora.EXPORTS) == names
+
+
+def mk(T=8, D=16, K=24, seg_off=(0, 3, 8), seg_adapter=(0, 1), rank=(4, 8), scale=(1.0, 2.0),
+       dtype=plora.PLORA_BF16):
+    return plora.Desc(T, D, K, np.array(seg_off), np.array(seg_adapter), np.array(rank),
+                      np.array(scale), dtype)
+
+
+def test_validate_codes():
+    ok = mk()
+    assert plora.plora_validate(ok) == 0
+    assert plora.plora_h_elems(ok) == 3 * 4 + 5 * 8
+    assert plora.plora_workspace_bytes(ok) > 0
+    bad = {
+        2: [mk(D=12), mk(K=20), mk(T=-1), mk(D=0)],                      # shape
+        3: [mk(seg_off=(1, 3, 8)), mk(seg_off=(0, 3, 7)), mk(seg_off=(0, 9, 8))],   # segments
+        4: [mk(seg_adapter=(0, 2)), mk(seg_adapter=(-2, 1))],            # adapter id
+        5: [mk(rank=(0, 8)), mk(rank=(4, 129))],                         # rank
+        8: [mk(dtype=7)],                                                # dtype
+    }
+    for code, cases in bad.items():
+        for d in cases:
+            assert plora.plora_validate(d) == code, (code, d)
+            assert plora.plora_h_elems(d) == 0 and plora.plora_workspace_bytes(d) == 0
+            assert plora.plora_status_string(code)
+    # fp32 has no multiple-of-8 rule; empty batch and base-only segments are legal
+    assert plora.plora_validate(mk(D=12, K=20, dtype=plora.PLORA_F32)) == 0
+    assert plora.plora_validate(mk(T=0, seg_off=(0, 0, 0))) == 0
+    assert plora.plora_validate(mk(seg_adapter=(-1, -1))) == 0
+    assert plora.plora_validate(plora.Desc(0, 16, 16, np.zeros(1), np.zeros(0), np.zeros(0), np.zeros(0), 0)) == 0
+
+
+def test_entry_points_reject_before_touching_the_device():
+    """NULL / misaligned pointers and a short workspace are refused with their codes; nothing here
+    needs a device because validation comes first."""
+    L = plora.lib()
+    d = mk()
+    tab = (C.c_void_p * 2)(0x1000, 0x2000)
+    tabp = C.cast(tab, C.c_void_p)
+    ws_bytes = plora.plora_workspace_bytes(d)
+    fwd = lambda x, W, A, B, y, h, ws, n: L.plora_linear_fwd(d.ref, x, W, A, B, y, h, ws, n, None)
+    assert fwd(None, 0x1000, tabp, tabp, 0x1000, None, 0x1000, ws_bytes) == 1
+    assert fwd(0x1000, None, tabp, tabp, 0x1000, None, 0x1000, ws_bytes) == 1
+    assert fwd(0x1000, 0x1000, None, tabp, 0x1000, None, 0x1000, ws_bytes) == 1
+    assert fwd(0x1008, 0x1000, tabp, tabp, 0x1000, None, 0x1000, ws_bytes) == 6
+    assert fwd(0x1000, 0x1000, tabp, tabp, 0x1000, None, None, ws_bytes) == 7
+    assert fwd(0x1000, 0x1000, tabp, tabp, 0x1000, None, 0x1000, ws_bytes - 1) == 7
+    assert fwd(0x1000, 0x1000, tabp, tabp, 0x1000, None, 0x1010, ws_bytes) == 6     # workspace needs 256
+    assert fwd(0x1000, 0x1000, tabp, tabp, None, None, 0x1000, ws_bytes) == 1
+    bad = mk(rank=(4, 200))
+    assert L.plora_linear_fwd(bad.ref, 0x1000, 0x1000, tabp, tabp, 0x1000, None, 0x1000, 1 << 30, None) == 5
+    bwd = lambda dy, dx, dA, dB: L.plora_linear_bwd(d.ref, 0x1000, 0x1000, tabp, tabp, dy, None, dx, dA, dB,
+                                                    0x1000, ws_bytes, None)
+    assert bwd(None, 0x1000, tabp, tabp) == 1
+    assert bwd(0x1000, 0x1000, tabp, None) == 1          # dA without dB
+    assert bwd(0x1004, 0x1000, tabp, tabp) == 6
+    nulltab = (C.c_void_p * 2)(0x1000, None)
+    assert bwd(0x1000, 0x1000, C.cast(nulltab, C.c_void_p), tabp) == 1
+
+
+def brute_force_metadata(seg_off, seg_adapter, rank, block_rows):
+    """Row by row: scan for the segment of each row, open a new block when the segment changes
+    or the block is full."""
+    T = seg_off[-1]
+    h_off, acc = [], 0
+    for s in range(len(seg_adapter)):
+        h_off.append(acc)
+        if seg_adapter[s] >= 0:
+            acc += (seg_off[s + 1] - seg_off[s]) * rank[seg_adapter[s]]
+    h_off.append(acc)
+    blocks = []
+    for t in range(T):
+        s = next(q for q in range(len(seg_adapter)) if seg_off[q] <= t < seg_off[q + 1])
+        if blocks and blocks[-1][2] == s and blocks[-1][1] < block_rows:
+            blocks[-1][1] += 1
+        else:
+            blocks.append([t, 1, s, seg_adapter[s]])
+    return np.array(h_off, dtype=np.int64), np.array(blocks, dtype=np.int32).reshape(-1, 4)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_metadata_equals_brute_force(seed):
+    rng = np.random.default_rng(seed)
+    n_ad = int(rng.integers(1, 6))
+    n_seg = int(rng.integers(1, 9))
+    lens = rng.integers(0, 300, size=n_seg)
+    lens[rng.integers(n_seg)] = 0
+    seg_off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    seg_adapter = rng.integers(-1, n_ad, size=n_seg).astype(np.int32)
+    rank = rng.integers(1, 129, size=n_ad).astype(np.int32)
+    d = plora.Desc(int(seg_off[-1]), 64, 64, seg_off, seg_adapter, rank, np.ones(n_ad), plora.PLORA_BF16)
+    for block_rows in (1, 64, 256):
+        h_off, blocks = plora.plora_build_metadata(d, block_rows)
+        h_ref, b_ref = brute_force_metadata(seg_off.tolist(), seg_adapter.tolist(), rank.tolist(), block_rows)
+        assert np.array_equal(h_off, h_ref)
+        assert np.array_equal(blocks, b_ref)
+    assert plora.plora_h_elems(d) == int(h_ref[-1])
+
+
+def test_metadata_int64_offsets():
+    """The activation offsets are 64-bit: 2^31 elements are crossed without wrapping."""
+    seg_off = np.array([0, 2 ** 24, 2 ** 25], dtype=np.int32)
+    d = plora.Desc(2 ** 25, 64, 64, seg_off, np.array([0, 1]), np.array([128, 128]), np.ones(2), plora.PLORA_BF16)
+    h_off, _ = plora.plora_build_metadata(d, 1 << 20)
+    assert h_off.tolist() == [0, 2 ** 31, 2 ** 32]
