@@ -1,0 +1,172 @@
+#!/usr/bin/env python3
+"""Benchmark of the packed multi-LoRA linear layer (forward + backward) on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch of synthetic input: plora_linear_fwd
+followed by plora_linear_bwd on the Llama-3-8B-shaped q_proj configuration (d_in = d_out = 4096,
+bf16, 4 adapters of rank 8/16/32/64 with 2048 tokens each), inputs resident in HBM.
+
+Prints ONE JSON line: whole-step TFLOP/s (FLOPs = 4 T D K + 6 (D+K) sum(L r)), tokens/s, the
+roofline of the dominant kernel (the forward base GEMM with the fused expand, timed with HIP events
+on its own stream inside a second pass of the same steps), the other kernels' rates, and the fp64
+CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "tests")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
+PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default: the headline one)")
+    ap.add_argument("--linear", type=int, default=0, help="which linear of the configuration")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2508_02932_amd import plora
+    from paper_2508_02932_amd import workloads as wl
+    import gpu_harness as gh
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    plora.lib()
+
+    lin = wl.config(args.config)[args.linear]
+    lay = lin.layout
+    T, D, K = lay.T, lin.D, lin.K
+    e = 2 if lin.dtype == "bf16" else 4
+    t = lin.tensors()
+    dp = gh.upload(lin, t)
+    sum_Lr = lay.sum_Lr()
+    R = int(sum(int(r) for r in lay.rank))
+    flops = lin.flops_fwd_bwd()
+
+    def step():
+        plora.plora_linear_fwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.y, dp.h, dp.ws)
+        plora.plora_linear_bwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.dy, dp.h, dp.dx, dp.dA, dp.dB, dp.ws)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # second pass of the same steps with every kernel bracketed by HIP events on its stream
+    plora.plora_set_kernel_timing(True)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    kern = {}
+    for name in plora.KERNEL_CLASSES:
+        ms, n = plora.plora_kernel_time(name)
+        kern[name] = (ms / n) if n else None
+    plora.plora_set_kernel_timing(False)
+
+    # algorithmic work per launch of each kernel (true ranks, nothing padded)
+    alg = {
+        "gemm_fwd": ("mfma", 2.0 * T * D * K + 2.0 * K * sum_Lr),
+        "gemm_dx": ("mfma", 2.0 * T * D * K + 2.0 * D * sum_Lr),
+        "shrink": ("hbm", T * D * e + D * R * e + sum_Lr * 4.0),
+        "dh": ("hbm", T * K * e + R * K * e + sum_Lr * 4.0),
+        "db": ("hbm", T * K * e + sum_Lr * 4.0 + R * K * 4.0),
+        "da": ("hbm", T * D * e + sum_Lr * 4.0 + D * R * 4.0),
+    }
+    kernels = {}
+    for name, (bound, work) in alg.items():
+        ms = kern.get(name)
+        if not ms:
+            continue
+        if bound == "mfma":
+            a = work / (ms * 1e-3) / 1e12
+            kernels[name] = {"ms": round(ms, 4), "bound": bound, "achieved": round(a, 1), "unit": "TFLOP/s",
+                             "frac": round(a / PEAK_BF16_MFMA_TFLOPS, 4)}
+        else:
+            a = work / (ms * 1e-3) / 1e9
+            kernels[name] = {"ms": round(ms, 4), "bound": bound, "achieved": round(a, 1), "unit": "GB/s",
+                             "frac": round(a / PEAK_HBM_GBS, 4)}
+    if kern.get("pack"):
+        kernels["pack"] = {"ms": round(kern["pack"], 4)}
+    # when the saved activation is handed to backward, class "shrink" of the last call is the
+    # conversion kernel; the forward shrink is what the roofline entry should describe
+    dom = kernels.get("gemm_fwd", {})
+    roofline = {"kernel": "k_gemm<forward> (x W with fused scale*h*B_k)", "bound": "mfma",
+                "achieved": dom.get("achieved"), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": dom.get("frac"), "traffic": None,
+                "avg_launch_ms": dom.get("ms")}
+
+    cpu = None
+    if not args.no_cpu:
+        import oracle
+        from util import make_problem
+        p = make_problem(oracle, lin, t)
+        rng = np.random.default_rng(0)
+        cores = oracle.loops.threads()
+
+        def rows_time(n):
+            rows = np.sort(rng.choice(T, size=min(n, T), replace=False))
+            a = time.perf_counter()
+            oracle.loops.fwd_rows(p, rows)
+            oracle.loops.bwd_rows(p, t.dy, rows)
+            return time.perf_counter() - a, len(rows)
+
+        probe_s, probe_n = rows_time(2 * cores)
+        n_rows = int(max(2 * cores, min(T, 12.0 / max(probe_s / probe_n, 1e-6))))
+        rows_s, n_rows = rows_time(n_rows)
+        a = time.perf_counter()
+        k_big = int(np.argmax(lay.rank))
+        oracle.loops.grad_adapter(p, t.dy, k_big)
+        grad_s = time.perf_counter() - a
+        # whole-step estimate: row part scaled to T rows; weight-gradient part scaled by sum(L r)
+        Lr_big = sum(int(lay.seg_off[s + 1] - lay.seg_off[s]) * int(lay.rank[k_big])
+                     for s in range(lay.n_seg) if lay.seg_adapter[s] == k_big)
+        est_step_s = rows_s * (T / n_rows) + grad_s * (sum_Lr / max(Lr_big, 1))
+        cpu = {"value": round(flops / est_step_s / 1e12, 6), "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
+               "tokens_per_s": round(T / est_step_s, 2),
+               "sample": f"fp64 scalar-loop oracle: y and dx of {n_rows} random rows of {T} ({rows_s:.1f} s) plus "
+                         f"dA, dB of the rank-{int(lay.rank[k_big])} adapter ({grad_s:.1f} s); whole step extrapolated"}
+
+    out = {
+        "metric": "packed multi-LoRA layer fwd+bwd TFLOP/s",
+        "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
+        "unit": "TFLOP/s",
+        "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if lin.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"config {args.config} / {lin.name}: d_in={D} d_out={K} T={T} "
+                               f"adapters={lay.n_adapters} ranks={sorted(set(int(r) for r in lay.rank))}",
+                   "tokens": T, "d_in": D, "d_out": K, "n_adapters": lay.n_adapters,
+                   "flops_per_step": flops},
+        "frac_of_bf16_mfma_peak": round(flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -137,15 +137,16 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
                               void *hip_stream);
 
 /*
- * Timing hook for benchmarks: when enabled (non-zero), every kernel of later calls is bracketed
- * by HIP events on its own stream, and plora_last_kernel_ms returns the duration of the named
- * kernel class in the most recent fwd or bwd call (after the caller has synchronised the
- * stream).  Classes: 0 base GEMM forward, 1 dX GEMM, 2 shrink, 3 dH, 4 dB, 5 dA, 6 packing of
- * the small operands, 7 W transpose.  Returns a negative value if nothing was recorded.
- * Not thread-safe; meant for bench.py only.
+ * Timing hook for benchmarks.  While enabled (non-zero), every kernel class of every fwd / bwd call
+ * is bracketed by a pair of HIP events recorded on the call's own stream.  Enabling clears earlier
+ * records; at most 16384 brackets are kept.  plora_kernel_time sums the recorded durations of
+ * one class (milliseconds) and counts them; the caller must have synchronised the streams first.
+ * Classes: 0 base GEMM forward (with the fused expand), 1 dX GEMM (with the fused low-rank
+ * term), 2 shrink, 3 dH, 4 dB, 5 dA, 6 packing of A_k, 7 conversion of a saved activation into
+ * the transposed bf16 operand of dB.  Returns 0, or -1 on a bad argument or event error.  Not thread-safe.
  */
 void plora_set_kernel_timing(int enabled);
-float plora_last_kernel_ms(int kernel_class);
+int plora_kernel_time(int kernel_class, float *total_ms, int *count);
 
 #ifdef __cplusplus
 }

@@ -103,24 +103,29 @@ static void build_meta(const plora_desc *d, HostMeta &m)
 }
 
 // ---- bench-only kernel timing ------------------------------------------------------------------
+// Every kernel class of a call is bracketed by a pair of HIP events recorded on the call's own
+// stream; pairs come from a pool that is filled while timing is enabled and summed on request.
 constexpr int kClasses = 8;
+constexpr int kMaxPairs = 16384;
 static int g_timing = 0;
-static hipEvent_t g_ev[kClasses][2];
-static bool g_ev_made = false;
-static bool g_ev_used[kClasses];
+static std::vector<hipEvent_t> g_pool;            // 2 events per pair, created on demand
+static std::vector<int> g_pair_class;             // class of each recorded pair
 
 struct Bracket {
-    int cls; hipStream_t st; bool on;
-    Bracket(int c, hipStream_t s) : cls(c), st(s), on(g_timing != 0)
+    int pair; hipStream_t st;
+    Bracket(int cls, hipStream_t s) : pair(-1), st(s)
     {
-        if (!on) return;
-        if (!g_ev_made) {
-            for (int i = 0; i < kClasses; ++i) { (void)hipEventCreate(&g_ev[i][0]); (void)hipEventCreate(&g_ev[i][1]); }
-            g_ev_made = true;
+        if (!g_timing || (int)g_pair_class.size() >= kMaxPairs) return;
+        pair = (int)g_pair_class.size();
+        if ((int)g_pool.size() < 2 * (pair + 1)) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) { pair = -1; return; }
+            g_pool.push_back(a); g_pool.push_back(b);
         }
-        (void)hipEventRecord(g_ev[cls][0], st);
+        g_pair_class.push_back(cls);
+        (void)hipEventRecord(g_pool[2 * pair], st);
     }
-    ~Bracket() { if (on) { (void)hipEventRecord(g_ev[cls][1], st); g_ev_used[cls] = true; } }
+    ~Bracket() { if (pair >= 0) (void)hipEventRecord(g_pool[2 * pair + 1], st); }
 };
 
 #define PL_TRY(expr) do { hipError_t e__ = (expr); if (e__ != hipSuccess) return PLORA_ERR_HIP; } while (0)
@@ -232,15 +237,21 @@ int64_t plora_build_metadata(const plora_desc *desc, int32_t block_rows, int64_t
 void plora_set_kernel_timing(int enabled)
 {
     g_timing = enabled;
-    for (int i = 0; i < kClasses; ++i) g_ev_used[i] = false;
+    g_pair_class.clear();
 }
 
-float plora_last_kernel_ms(int cls)
+int plora_kernel_time(int cls, float *total_ms, int *count)
 {
-    if (cls < 0 || cls >= kClasses || !g_ev_made || !g_ev_used[cls]) return -1.f;
-    float ms = -1.f;
-    if (hipEventElapsedTime(&ms, g_ev[cls][0], g_ev[cls][1]) != hipSuccess) return -1.f;
-    return ms;
+    if (cls < 0 || cls >= kClasses || !total_ms || !count) return -1;
+    float tot = 0.f; int n = 0;
+    for (size_t p = 0; p < g_pair_class.size(); ++p) {
+        if (g_pair_class[p] != cls) continue;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, g_pool[2 * p], g_pool[2 * p + 1]) != hipSuccess) return -1;
+        tot += ms; ++n;
+    }
+    *total_ms = tot; *count = n;
+    return 0;
 }
 
 plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void *W,
@@ -255,7 +266,6 @@ plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void 
     if (desc->T == 0) return PLORA_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
-    for (int i = 0; i < kClasses; ++i) g_ev_used[i] = false;
 
     MetaView mv;
     PL_TRY(upload_meta(m, ws, st, mv));
@@ -302,7 +312,6 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
-    for (int i = 0; i < kClasses; ++i) g_ev_used[i] = false;
     const bool lora = m.hdr.n_blocks > 0;
     const bool any_w = want_w && desc->n_adapters > 0;
     if (desc->T == 0 && !any_w) return PLORA_OK;
@@ -338,7 +347,7 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
         const bool need_shrink = any_w && !h_saved;
         { Bracket b(6, st); PL_TRY(launch_pack_bf16(mv, m.hdr, at, ap, need_shrink, dx != nullptr, st)); }
         if (any_w) {
-            Bracket b(2, st);
+            Bracket b(h_saved ? 7 : 2, st);
             if (h_saved) PL_TRY(launch_h_to_zt(mv, m.hdr, h_saved, zt_h, st));
             else PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, nullptr, nullptr, zt_h, false, st));
         }

@@ -20,11 +20,11 @@ LIB_PATH = os.path.join(_HERE, "libplora.so")
 PLORA_BF16, PLORA_F32 = 0, 1
 PLORA_OK = 0
 PLORA_MAX_RANK, PLORA_MAX_ADAPTERS, PLORA_MAX_SEGMENTS = 128, 256, 1024
-KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "pack": 6}
+KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "pack": 6, "convert": 7}
 
 EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_workspace_bytes",
            "plora_build_metadata", "plora_linear_fwd", "plora_linear_bwd",
-           "plora_set_kernel_timing", "plora_last_kernel_ms"]
+           "plora_set_kernel_timing", "plora_kernel_time"]
 
 
 class PloraError(RuntimeError):
@@ -66,8 +66,8 @@ def lib():
         L.plora_linear_bwd.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
         L.plora_set_kernel_timing.restype = None
         L.plora_set_kernel_timing.argtypes = [C.c_int]
-        L.plora_last_kernel_ms.restype = C.c_float
-        L.plora_last_kernel_ms.argtypes = [C.c_int]
+        L.plora_kernel_time.restype = C.c_int
+        L.plora_kernel_time.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
         _lib = L
     return _lib
 
@@ -177,7 +177,11 @@ def plora_set_kernel_timing(enabled: bool) -> None:
     lib().plora_set_kernel_timing(1 if enabled else 0)
 
 
-def plora_last_kernel_ms(kernel_class) -> float:
+def plora_kernel_time(kernel_class):
+    """(total milliseconds, number of brackets) recorded for one kernel class since timing was enabled."""
     if isinstance(kernel_class, str):
         kernel_class = KERNEL_CLASSES[kernel_class]
-    return float(lib().plora_last_kernel_ms(int(kernel_class)))
+    ms, n = C.c_float(0), C.c_int(0)
+    if lib().plora_kernel_time(int(kernel_class), C.byref(ms), C.byref(n)) != 0:
+        raise PloraError(-1, "plora_kernel_time failed")
+    return float(ms.value), int(n.value)
