@@ -266,6 +266,8 @@ int plora_oracle_grad_adapter(const plora_oracle_problem *p, const float *dy, in
     if (k < 0 || k >= p->n_adapters || !dy || !dA || !dB)
         return ORACLE_BAD_ARG;
     const int32_t r = p->rank[k];
+    if (r > 256)
+        return ORACLE_BAD_ARG;
     const int64_t D = p->D, K = p->K;
 
     /* tokens of adapter k, in order */
@@ -288,23 +290,33 @@ int plora_oracle_grad_adapter(const plora_oracle_problem *p, const float *dy, in
         low_rank_gradient(p, dy, tok[q], k, g + q * r);
     }
 
+    /* Each output element is one sum over the adapter's tokens in token order; the rank index is
+     * the innermost loop only so that x and dy are walked once per (column, token). */
 #pragma omp parallel for schedule(static)
-    for (int64_t i = 0; i < D; ++i)
-        for (int32_t j = 0; j < r; ++j) {
-            double acc = 0.0;
-            for (int64_t q = 0; q < n_tok; ++q)
-                acc += (double)p->x[tok[q] * D + i] * g[q * r + j];
-            dA[i * r + j] = acc;
+    for (int64_t i = 0; i < D; ++i) {
+        double *acc = dA + i * r;
+        for (int32_t j = 0; j < r; ++j)
+            acc[j] = 0.0;
+        for (int64_t q = 0; q < n_tok; ++q) {
+            const double xv = (double)p->x[tok[q] * D + i];
+            for (int32_t j = 0; j < r; ++j)
+                acc[j] += xv * g[q * r + j];
         }
+    }
 
 #pragma omp parallel for schedule(static)
-    for (int64_t n = 0; n < K; ++n)
-        for (int32_t j = 0; j < r; ++j) {
-            double acc = 0.0;
-            for (int64_t q = 0; q < n_tok; ++q)
-                acc += h[q * r + j] * (double)dy[tok[q] * K + n];
-            dB[(int64_t)j * K + n] = (double)p->scale[k] * acc;
+    for (int64_t n = 0; n < K; ++n) {
+        double acc[256];
+        for (int32_t j = 0; j < r; ++j)
+            acc[j] = 0.0;
+        for (int64_t q = 0; q < n_tok; ++q) {
+            const double dv = (double)dy[tok[q] * K + n];
+            for (int32_t j = 0; j < r; ++j)
+                acc[j] += h[q * r + j] * dv;
         }
+        for (int32_t j = 0; j < r; ++j)
+            dB[(int64_t)j * K + n] = (double)p->scale[k] * acc[j];
+    }
 
     free(h);
     free(g);

@@ -40,6 +40,7 @@ struct HostMeta {
     std::vector<AdapterInfo> ad;
     WorkspaceLayout ws;
     size_t h_elems = 0, hb_elems = 0, zt_elems = 0, at_elems = 0, ap_elems = 0;
+    int r16_total = 0, n_active = 0, split_dA = 1, split_dB = 1;
 };
 
 // The segment-packing metadata builder (host).  Pure integer work.
@@ -50,6 +51,7 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     m.seg.resize(d->n_seg);
     m.ad.resize(d->n_adapters);
     int64_t at = 0, ap = 0;
+    int32_t r16_off = 0;
     for (int32_t k = 0; k < d->n_adapters; ++k) {
         AdapterInfo &a = m.ad[k];
         std::memset(&a, 0, sizeof(a));
@@ -59,6 +61,7 @@ static void build_meta(const plora_desc *d, HostMeta &m)
         a.scale = d->scale[k];
         a.at_off = at; at += (int64_t)a.r16 * d->d_in;
         a.ap_off = ap; ap += (int64_t)a.rp * d->d_in;
+        a.r16_off = r16_off; r16_off += a.r16;
     }
     int64_t h = 0, hb = 0, zt = 0;
     int32_t blk = 0;
@@ -82,6 +85,16 @@ static void build_meta(const plora_desc *d, HostMeta &m)
         }
     }
     m.hdr.n_blocks = blk;
+    m.r16_total = r16_off;
+    {
+        std::vector<char> seen(d->n_adapters, 0);
+        for (int32_t s = 0; s < d->n_seg; ++s)
+            if (m.seg[s].adapter >= 0 && m.seg[s].row1 > m.seg[s].row0) seen[m.seg[s].adapter] = 1;
+        m.n_active = 0;
+        for (char c : seen) m.n_active += c;
+    }
+    m.split_dA = tokc_splits(m.hdr, d->d_in, m.n_active);
+    m.split_dB = tokc_splits(m.hdr, d->d_out, m.n_active);
     m.h_elems = (size_t)h; m.hb_elems = (size_t)hb; m.zt_elems = (size_t)zt;
     m.at_elems = (size_t)at; m.ap_elems = (size_t)ap;
 
@@ -98,7 +111,12 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     w.zt_g = o; o = align_up(o + (bf ? m.zt_elems * 2 : 0), 256);
     w.hf = o;   o = align_up(o + m.h_elems * 4, 256);
     w.gf = o;   o = align_up(o + (bf ? 0 : m.h_elems * 4), 256);
-    w.wt = o;
+    w.part = o; o = align_up(o + (bf ? (size_t)kSkinnyMaxSplits * blk * kSkinnyRows * m.hdr.max_r16 * 4 : 0), 256);
+    {
+        const size_t a_bytes = m.split_dA > 1 ? (size_t)m.split_dA * m.r16_total * d->d_in * 4 : 0;
+        const size_t b_bytes = m.split_dB > 1 ? (size_t)m.split_dB * m.r16_total * d->d_out * 4 : 0;
+        w.wpart = o; o = align_up(o + (bf ? (a_bytes > b_bytes ? a_bytes : b_bytes) : 0), 256);
+    }
     w.total = o + 256;
 }
 
@@ -281,10 +299,11 @@ plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void 
     }
 
     void *at = ws + m.ws.at, *hb = ws + m.ws.hb;
+    float *part = reinterpret_cast<float *>(ws + m.ws.part);
     if (lora) {
         { Bracket b(6, st); PL_TRY(launch_pack_bf16(mv, m.hdr, at, nullptr, true, false, st)); }
         { Bracket b(2, st);
-          PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, h_saved, hb, nullptr, false, st)); }
+          PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, h_saved, hb, nullptr, false, st)); }
     }
     { Bracket b(0, st);
       PL_TRY(launch_gemm_bf16(mv, m.hdr, true, x, W, hb, nullptr, ws + m.ws.zero, y, st)); }
@@ -343,20 +362,22 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
 
     void *at = ws + m.ws.at, *ap = ws + m.ws.ap, *gb = ws + m.ws.hb;
     void *zt_h = ws + m.ws.zt_h, *zt_g = ws + m.ws.zt_g;
+    float *part = reinterpret_cast<float *>(ws + m.ws.part);
+    float *wpart = reinterpret_cast<float *>(ws + m.ws.wpart);
     if (lora) {
         const bool need_shrink = any_w && !h_saved;
         { Bracket b(6, st); PL_TRY(launch_pack_bf16(mv, m.hdr, at, ap, need_shrink, dx != nullptr, st)); }
         if (any_w) {
             Bracket b(h_saved ? 7 : 2, st);
             if (h_saved) PL_TRY(launch_h_to_zt(mv, m.hdr, h_saved, zt_h, st));
-            else PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, nullptr, nullptr, zt_h, false, st));
+            else PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, nullptr, nullptr, zt_h, false, st));
         }
         { Bracket b(3, st);
-          PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, nullptr, gb, any_w ? zt_g : nullptr, true, st)); }
+          PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, ws + m.ws.zero, part, nullptr, gb, any_w ? zt_g : nullptr, true, st)); }
     }
     if (any_w) {
-        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + m.ws.zero, st)); }
-        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + m.ws.zero, st)); }
+        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + m.ws.zero, wpart, m.split_dB, m.r16_total, st)); }
+        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + m.ws.zero, wpart, m.split_dA, m.r16_total, st)); }
     }
     if (dx && desc->T > 0) {
         Bracket b(1, st);

@@ -10,11 +10,13 @@
 
 namespace plora {
 
-constexpr int kSkinnyRows = 64;    // token block of the shrink / dH kernel (never straddles a segment)
+constexpr int kSkinnyRows = 128;   // token block of the shrink / dH kernel (never straddles a segment)
 constexpr int kRankPadGemm = 64;   // ranks are padded to one K-step of the GEMM in the bf16 side buffers
 constexpr int kRankPadMfma = 16;   // ranks are padded to one MFMA block in the skinny kernels
 constexpr int kTokPad = 64;        // segment lengths are padded to this in the transposed side buffers
 constexpr int kZeroBytes = 1024;   // zero page at the head of the workspace
+constexpr int kTokMaxSplits = 8;    // the dA / dB kernels split the token walk over at most this many workgroups
+constexpr int kSkinnyMaxSplits = 8; // the skinny kernels split the contraction over at most this many workgroups
 
 // One entry per segment of the call (empty and base-only segments included).
 struct SegInfo {
@@ -40,6 +42,8 @@ struct AdapterInfo {
     float scale;
     int64_t at_off;       // element offset of A^T  [r16][d_in]  in the packed-A^T buffer
     int64_t ap_off;       // element offset of A    [d_in][rp]   in the padded-A buffer
+    int32_t r16_off;      // sum of r16 over the adapters before this one (row offset in dA / dB partial tiles)
+    int32_t pad_;
 };
 
 struct MetaHeader {
@@ -58,7 +62,7 @@ struct MetaView {
 
 // Byte offsets of the workspace regions, each 256-byte aligned.
 struct WorkspaceLayout {
-    size_t zero, meta, at, ap, hb, zt_h, zt_g, hf, gf, wt, total;
+    size_t zero, meta, at, ap, hb, zt_h, zt_g, hf, gf, part, wpart, total;
     size_t meta_bytes;
 };
 
@@ -75,10 +79,12 @@ hipError_t launch_pack_bf16(const MetaView &mv, const MetaHeader &h, void *at, v
                             bool want_ap, hipStream_t st);
 // Skinny product over token blocks: acc[t][j] = sum_c S[t][c] * Bm_k[j][c]  (c < C).
 //   mode 0 (shrink): S = x (C = d_in), Bm_k = packed A_k^T;  mode 1 (dH): S = dy (C = d_out), Bm_k = B_k.
-//   Writes (each optional): hf fp32 [len][r] unscaled; hb bf16 [len][rp] = mult*acc; zt bf16 [r16][lp]
-//   transposed, = (scale_t ? mult : 1) * acc, where mult = scale_k.
+//   `part` receives the fp32 partial tiles of the contraction splits; a finishing kernel sums them and
+//   writes (each optional): hf fp32 [len][r] (unscaled in mode 0); hb bf16 [len][rp] = scale_k*acc;
+//   zt bf16 [r16][lp] transposed, = (zt_scaled ? scale_k : 1) * acc.
 hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode, const void *S, int64_t C,
-                              const void *at, float *hf, void *hb, void *zt, bool zt_scaled, hipStream_t st);
+                              const void *at, const void *zero, float *part, float *hf, void *hb, void *zt,
+                              bool zt_scaled, hipStream_t st);
 // Transposed bf16 copy of a saved fp32 activation: zt[j][t] = bf16(h[t][j]).
 hipError_t launch_h_to_zt(const MetaView &mv, const MetaHeader &h, const float *hf, void *zt, hipStream_t st);
 // C[T][N] = S[T][Kd] * Wop + side[T][rp] * ext_k, rounded to bf16.
@@ -88,8 +94,12 @@ hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool forwar
                             const void *side, const void *ap, const void *zero, void *C, hipStream_t st);
 // Token contraction: out_k = mult * sum_t S[t][c] * zt[j][t] over all segments of adapter k.
 //   want_dA: S = x, out = dA_k[c][j], mult = 1;  else S = dy, out = dB_k[j][c], mult = scale_k.
+//   n_split > 1: the token walk is split, partial tiles go through `part` ([split][r16_total][C] fp32).
 hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool want_dA, const void *S,
-                                   int64_t C, const void *zt, const void *zero, hipStream_t st);
+                                   int64_t C, const void *zt, const void *zero, float *part, int n_split,
+                                   int r16_total, hipStream_t st);
+int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters);
+int skinny_splits(const MetaHeader &h, int64_t C);
 
 // fp32 path (fp64 accumulation) ---------------------------------------------------------------------
 hipError_t launch_f32_lowrank(const MetaView &mv, const MetaHeader &h, int mode, const float *S, int64_t C,

@@ -3,15 +3,21 @@
 //   dH      g_t = scale_k dy_t B_k^T (appendix C.2, case 2)
 // Both stream one big [T][C] matrix once (C = d_in or d_out) against a small per-adapter matrix
 // whose rows are output columns with the contraction index contiguous (A_k^T packed, or B_k as it
-// is).  They are bound by HBM; the arithmetic runs on 16x16x32 bf16 MFMA with fp32 accumulators so
-// that ranks up to 128 stay far below the matrix-core roof.  The rank is never tiled (appendix C.2:
-// tile the sequence and hidden dimensions, not the rank).
+// is).  They are bound by HBM, so the kernel is built around keeping bytes in flight: operands go
+// HBM -> LDS directly (global_load_lds) through a three-stage ring, the contraction is split over
+// workgroups when the batch has too few token blocks to fill the chip, and the arithmetic runs on
+// 16x16x32 bf16 MFMA with fp32 accumulators so that ranks up to 128 stay far below the
+// matrix-core roof.  The rank is never tiled (appendix C.2: tile the sequence and hidden
+// dimensions, not the rank).  Partial tiles of the splits are summed in a fixed order by a small
+// finishing kernel that also writes the bf16 copies the later kernels consume.
 #include "plora_internal.h"
 
 namespace plora {
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+
+#define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 
 __device__ inline uint16_t bf16_rne(float f)
 {
@@ -20,20 +26,36 @@ __device__ inline uint16_t bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-constexpr int kMB = kSkinnyRows / 16;   // 16-row MFMA blocks per token block
-constexpr int kMaxNB = PLORA_MAX_RANK / 16;
+constexpr int SK_BK = 64;                              // contraction elements per stage
+constexpr int SK_NST = 3;                              // ring stages
+constexpr int SK_XT = kSkinnyRows * SK_BK * 2;         // 16 KB: [128 tokens][64 k]
+constexpr int SK_XL = kSkinnyRows / 8 / 4;             // token-tile load instructions per wave per stage
+constexpr int SK_MB = kSkinnyRows / 16 / 4;            // 16-token MFMA blocks per wave
+constexpr int SK_MAXNB = PLORA_MAX_RANK / 16;
 
-// One workgroup (4 waves) per token block of kSkinnyRows rows of one segment.  The four waves split
-// the contraction: wave w takes the 32-wide steps w, w+4, ...; each keeps the whole [64][r16] tile
-// in registers and the partial tiles are summed through LDS at the end.
-//   MODE 0: small matrix = packed A_k^T [r16][C] (rows >= r are zero),  MODE 1: B_k [r][C].
-__global__ void __launch_bounds__(256) k_skinny(MetaView mv, int mode, const uint16_t *__restrict__ S, int64_t C,
-                                               const uint16_t *__restrict__ at, float *__restrict__ hf,
-                                               uint16_t *__restrict__ hb, uint16_t *__restrict__ zt, int zt_scaled)
+// s_waitcnt vmcnt(n) for a wave-uniform runtime n (the instruction takes an immediate)
+__device__ inline void wait_vmcnt_dyn(int n)
 {
-    extern __shared__ float part[];   // [4][kSkinnyRows][LDP]
-    constexpr int NB = kMaxNB;
-    const int LDP = mv.hdr->max_r16 + 1;
+#define W_(N) case N: __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14)); break;
+    switch (n) {
+        W_(0) W_(1) W_(2) W_(3) W_(4) W_(5) W_(6) W_(7) W_(8) W_(9) W_(10) W_(11) W_(12) W_(13) W_(14) W_(15)
+        W_(16) W_(17) W_(18)
+    default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+    }
+#undef W_
+}
+
+// One workgroup (4 waves) per (token block of 128 rows of one segment, slice of the contraction).
+// Stage = 64 contraction elements: the token tile [128][64] and the small-matrix tile [r16][64]
+// land in LDS by direct loads (16-byte chunks XOR-swizzled by row so that MFMA operand reads are
+// conflict free).  Wave w owns tokens 32w..32w+31 and every rank block, so nothing is reduced
+// across waves.  Output: the fp32 partial tile [128][r16] of this slice.
+//   mode 0: small matrix = packed A_k^T [r16][C] (rows >= r are zero),  mode 1: B_k [r][C].
+__global__ void __launch_bounds__(256) k_skinny(MetaView mv, int mode, const uint16_t *__restrict__ S, int C,
+                                               const uint16_t *__restrict__ at, const uint16_t *__restrict__ zero,
+                                               float *__restrict__ part, int stages_per_split)
+{
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int blk = blockIdx.x;
     const int n_seg = mv.hdr->n_seg;
     int s = 0;
@@ -44,110 +66,215 @@ __global__ void __launch_bounds__(256) k_skinny(MetaView mv, int mode, const uin
     const SegInfo g = mv.seg[s];
     const AdapterInfo a = mv.ad[g.adapter];
     const int t0 = (blk - g.blk0) * kSkinnyRows;
-    const int len = g.row1 - g.row0;
-    const int nt = (len - t0 < kSkinnyRows) ? len - t0 : kSkinnyRows;
+    const int nt = (g.row1 - g.row0 - t0 < kSkinnyRows) ? g.row1 - g.row0 - t0 : kSkinnyRows;
     const int nb = g.r16 / 16;
+    const int max_r16 = mv.hdr->max_r16;
+    const int stage_bytes = SK_XT + max_r16 * SK_BK * 2;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int lm = lane & 15, kg = lane >> 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
+
+    const int n_stage_all = (C + SK_BK - 1) / SK_BK;
+    const int st0 = blockIdx.y * stages_per_split;
+    int n_st = n_stage_all - st0;
+    n_st = n_st < stages_per_split ? n_st : stages_per_split;
+    if (n_st < 0) n_st = 0;
 
     const uint16_t *Bm = (mode == 0) ? at + a.at_off : static_cast<const uint16_t *>(a.B);
-    const int brows = (mode == 0) ? g.r16 : g.r;     // rows of the small matrix that may be read
+    const int brows = (mode == 0) ? g.r16 : g.r;     // rows of the small matrix that exist
 
-    const uint16_t *xrow[kMB];
-    bool xok[kMB];
+    // ---- loader: every load instruction moves 8 rows x 128 bytes; lane -> (row 8q + lane/8, slot
+    // lane%8); slot c' of row u holds chunk c' ^ ((u >> 1) & 7).  Token tile: 16 instructions, wave w
+    // issues w, w+4, w+8, w+12.  Small-matrix tile: r16/8 instructions, wave w issues w, w+4, ...
+    const int lrow = lane >> 3;
+    const uint16_t *xp[SK_XL];
+    bool xok[SK_XL];
+    int xchunk[SK_XL];
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb) {
-        const int tt = mb * 16 + lm;
-        xok[mb] = tt < nt;
-        xrow[mb] = S + (int64_t)(g.row0 + t0 + (xok[mb] ? tt : 0)) * C + kg * 8;
+    for (int jj = 0; jj < SK_XL; ++jj) {
+        const int u = (wave + 4 * jj) * 8 + lrow;
+        xchunk[jj] = (lane & 7) ^ ((u >> 1) & 7);
+        xok[jj] = u < nt;
+        xp[jj] = S + (int64_t)(g.row0 + t0 + (xok[jj] ? u : 0)) * C + (int64_t)st0 * SK_BK + xchunk[jj] * 8;
     }
-    const uint16_t *brow[NB];
-    bool bok[NB];
+    const int nbi = g.r16 / 8;                                    // small-matrix load instructions per stage
+    const int my_b = (nbi > wave) ? (nbi - wave + 3) / 4 : 0;     // ... of which this wave issues my_b
+    const uint16_t *bp[4];
+    bool bok[4];
+    int bchunk[4];
 #pragma unroll
-    for (int b = 0; b < NB; ++b) {
-        const int j = b * 16 + lm;
-        bok[b] = j < brows;
-        brow[b] = Bm + (int64_t)(bok[b] ? j : 0) * C + kg * 8;
+    for (int jj = 0; jj < 4; ++jj) {
+        const int u = (wave + 4 * jj) * 8 + lrow;
+        bchunk[jj] = (lane & 7) ^ ((u >> 1) & 7);
+        bok[jj] = u < brows;
+        bp[jj] = Bm + (int64_t)(bok[jj] ? u : 0) * C + (int64_t)st0 * SK_BK + bchunk[jj] * 8;
     }
+    const int lps = SK_XL + my_b;                                     // loads per stage issued by this wave
 
-    f32x4 acc[kMB][NB];
+    auto load16 = [&](const uint16_t *gp, uint32_t dst) {
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gp), "s"(dst));
+    };
+    auto issue = [&](int st) {       // stage index inside this split; ring slot st % SK_NST
+        const uint32_t base = lds_base + (st % SK_NST) * stage_bytes;
+        const int k0 = (st0 + st) * SK_BK;
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb)
+        for (int jj = 0; jj < SK_XL; ++jj) {
+            const bool ok = xok[jj] && (k0 + xchunk[jj] * 8 < C);
+            load16(ok ? xp[jj] + (int64_t)st * SK_BK : zero, base + (wave + 4 * jj) * 1024);
+        }
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[mb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int jj = 0; jj < 4; ++jj) {
+            if (jj < my_b) {
+                const bool ok = bok[jj] && (k0 + bchunk[jj] * 8 < C);
+                load16(ok ? bp[jj] + (int64_t)st * SK_BK : zero, base + SK_XT + (wave + 4 * jj) * 1024);
+            }
+        }
+    };
 
-    const int nks = (int)((C + 31) / 32);
-    const bf16x8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll 2
-    for (int ks = wave; ks < nks; ks += 4) {
-        const int64_t k0 = (int64_t)ks * 32;
-        const bool kok = k0 + kg * 8 < C;
-        bf16x8 xf[kMB], bfr[NB];
+    // ---- MFMA operands: lane (lm, kg) reads row lm of its block, chunk 4*ks + kg
+    const int lm = lane & 15, kg = lane >> 4;
+    int xoff[SK_MB];
 #pragma unroll
-        for (int mb = 0; mb < kMB; ++mb)
-            xf[mb] = (xok[mb] && kok) ? *reinterpret_cast<const bf16x8 *>(xrow[mb] + k0) : zero8;
+    for (int mb = 0; mb < SK_MB; ++mb) {
+        const int u = (wave * SK_MB + mb) * 16 + lm;
+        xoff[mb] = u * 128 + ((kg ^ ((u >> 1) & 7)) * 16);                  // ks*4 XORs in (bit 2 of the chunk)
+    }
+    int boff[SK_MAXNB];
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
-            bfr[b] = (b < nb && bok[b] && kok) ? *reinterpret_cast<const bf16x8 *>(brow[b] + k0) : zero8;
+    for (int b = 0; b < SK_MAXNB; ++b) {
+        const int u = b * 16 + lm;
+        boff[b] = SK_XT + u * 128 + ((kg ^ ((u >> 1) & 7)) * 16);
+    }
+    f32x4 acc[SK_MB][SK_MAXNB];
 #pragma unroll
-        for (int b = 0; b < NB; ++b) {
-            if (b < nb) {
+    for (int mb = 0; mb < SK_MB; ++mb)
 #pragma unroll
-                for (int mb = 0; mb < kMB; ++mb)
-                    acc[mb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mb], bfr[b], acc[mb][b], 0, 0, 0);
+        for (int b = 0; b < SK_MAXNB; ++b) acc[mb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int p = 0; p < SK_NST - 1; ++p)
+        if (p < n_st) issue(p);
+    for (int st = 0; st < n_st; ++st) {
+        const int ahead = (n_st - 1 - st < SK_NST - 2) ? n_st - 1 - st : SK_NST - 2;
+        wait_vmcnt_dyn(ahead * lps);             // this wave's loads of stage st have landed ...
+        __builtin_amdgcn_s_barrier();            // ... and everyone else's; ring slot (st-1) is free
+        if (st + SK_NST - 1 < n_st) issue(st + SK_NST - 1);
+        const char *sb = lds + (st % SK_NST) * stage_bytes;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 xf[SK_MB];
+#pragma unroll
+            for (int mb = 0; mb < SK_MB; ++mb) xf[mb] = *LDS_PTR(const bf16x8, sb + (xoff[mb] ^ (ks * 64)));
+#pragma unroll
+            for (int b = 0; b < SK_MAXNB; ++b) {
+                if (b < nb) {
+                    const bf16x8 bf = *LDS_PTR(const bf16x8, sb + (boff[b] ^ (ks * 64)));
+#pragma unroll
+                    for (int mb = 0; mb < SK_MB; ++mb)
+                        acc[mb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(xf[mb], bf, acc[mb][b], 0, 0, 0);
+                }
             }
         }
     }
 
-    // partial tiles -> LDS.  Lane holds column j = lm, rows 4*kg + i of each 16x16 block.
-    float *mine = part + (size_t)wave * kSkinnyRows * LDP;
+    // partial tile [128][r16] of this (block, split): lane holds column 16b + lm, rows 16*(2w+mb) + 4kg + i
+    float *dst = part + ((int64_t)blockIdx.y * gridDim.x + blk) * (kSkinnyRows * max_r16);
 #pragma unroll
-    for (int mb = 0; mb < kMB; ++mb)
+    for (int mb = 0; mb < SK_MB; ++mb)
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+        for (int b = 0; b < SK_MAXNB; ++b)
             if (b < nb) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    mine[(mb * 16 + kg * 4 + i) * LDP + b * 16 + lm] = acc[mb][b][i];
+                    dst[((wave * SK_MB + mb) * 16 + kg * 4 + i) * g.r16 + b * 16 + lm] = acc[mb][b][i];
             }
-    __syncthreads();
+}
 
-    auto total = [&](int tt, int j) -> float {
-        const float *p = part + tt * LDP + j;
-        return (p[0] + p[kSkinnyRows * LDP]) + (p[2 * kSkinnyRows * LDP] + p[3 * kSkinnyRows * LDP]);
-    };
-    const float mult = a.scale;
-    const int r = g.r;
-    if (hf) {   // fp32 [len][r], unscaled in mode 0 (saved activation), scaled in mode 1
+// Sums the partial tiles of the splits (fixed order) and writes, each optional:
+//   hf fp32 [len][r]   (mode 0: the activation itself; mode 1: scaled by scale_k)
+//   hb bf16 [len][rp]  scale_k * sum, zero beyond r           (K-extension operand of the GEMM)
+//   zt bf16 [r16][lp]  transposed, zero for padding tokens and rows >= r; scaled if zt_scaled
+__global__ void __launch_bounds__(256) k_skinny_finish(MetaView mv, int mode, const float *__restrict__ part,
+                                                      int n_split, float *__restrict__ hf, uint16_t *__restrict__ hb,
+                                                      uint16_t *__restrict__ zt, int zt_scaled)
+{
+    constexpr int FR = 16;                            // token rows per workgroup (grid.y slices of a block)
+    __shared__ float tile[FR][PLORA_MAX_RANK + 1];
+    const int blk = blockIdx.x;
+    const int n_seg = mv.hdr->n_seg;
+    int s = 0;
+    for (int q = 0; q < n_seg; ++q) {
+        const SegInfo gq = mv.seg[q];
+        if (gq.adapter >= 0 && gq.row1 > gq.row0 && blk >= gq.blk0) s = q;
+    }
+    const SegInfo g = mv.seg[s];
+    const float mult = mv.ad[g.adapter].scale;
+    const int tb = (blk - g.blk0) * kSkinnyRows;      // first token of the block inside the segment
+    const int r0 = blockIdx.y * FR;                   // first row of this slice inside the block
+    const int t0 = tb + r0;
+    int nt = g.row1 - g.row0 - t0;                    // valid tokens in this slice
+    nt = nt < 0 ? 0 : (nt < FR ? nt : FR);
+    if (t0 >= g.lp) return;                           // slice lies past the padded segment: nothing to write
+    const int r = g.r, r16 = g.r16;
+    const int64_t tile_elems = (int64_t)kSkinnyRows * mv.hdr->max_r16;
+    const int64_t split_stride = (int64_t)gridDim.x * tile_elems;
+    const float *src = part + (int64_t)blk * tile_elems + (int64_t)r0 * r16;
+    for (int e = threadIdx.x; e < FR * r16; e += 256) {
+        float v[kSkinnyMaxSplits];
+#pragma unroll
+        for (int sp = 0; sp < kSkinnyMaxSplits; ++sp) v[sp] = (sp < n_split) ? src[sp * split_stride + e] : 0.f;
+        float sum = v[0];
+#pragma unroll
+        for (int sp = 1; sp < kSkinnyMaxSplits; ++sp) sum += v[sp];
+        tile[e / r16][e % r16] = sum;
+    }
+    __syncthreads();
+    if (hf) {
         float *dst = hf + g.h_off + (int64_t)t0 * r;
         for (int e = threadIdx.x; e < nt * r; e += 256) {
-            const float v = total(e / r, e % r);
+            const float v = tile[e / r][e % r];
             dst[e] = (mode == 0) ? v : mult * v;
         }
     }
-    if (hb) {   // bf16 [len][rp], scaled, zero beyond r
+    if (hb) {
         uint16_t *dst = hb + g.hb_off + (int64_t)t0 * g.rp;
         for (int e = threadIdx.x; e < nt * g.rp; e += 256) {
             const int tt = e / g.rp, j = e % g.rp;
-            dst[e] = (j < r) ? bf16_rne(mult * total(tt, j)) : (uint16_t)0;
+            dst[e] = (j < r) ? bf16_rne(mult * tile[tt][j]) : (uint16_t)0;
         }
     }
-    if (zt) {   // bf16 [r16][lp] transposed, zero for padding tokens and rows >= r
+    if (zt) {
         uint16_t *dst = zt + g.zt_off + t0;
         const float zm = zt_scaled ? mult : 1.f;
-        for (int e = threadIdx.x; e < g.r16 * kSkinnyRows; e += 256) {
-            const int j = e / kSkinnyRows, tt = e % kSkinnyRows;
-            dst[(int64_t)j * g.lp + tt] = (j < r && tt < nt) ? bf16_rne(zm * total(tt, j)) : (uint16_t)0;
+        for (int e = threadIdx.x; e < r16 * FR; e += 256) {
+            const int j = e / FR, tt = e % FR;
+            dst[(int64_t)j * g.lp + tt] = (j < r && tt < nt) ? bf16_rne(zm * tile[tt][j]) : (uint16_t)0;
         }
     }
 }
 
+int skinny_splits(const MetaHeader &h, int64_t C)
+{
+    if (h.n_blocks == 0) return 1;
+    const int n_stage_all = (int)((C + SK_BK - 1) / SK_BK);
+    int want = (768 + h.n_blocks - 1) / h.n_blocks;          // aim at >= 3 workgroups per CU
+    int cap = n_stage_all / 8;                                // keep at least 8 stages per split
+    if (cap < 1) cap = 1;
+    if (want > cap) want = cap;
+    if (want > kSkinnyMaxSplits) want = kSkinnyMaxSplits;
+    if (want < 1) want = 1;
+    return want;
+}
+
 hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode, const void *S, int64_t C,
-                              const void *at, float *hf, void *hb, void *zt, bool zt_scaled, hipStream_t st)
+                              const void *at, const void *zero, float *part, float *hf, void *hb, void *zt,
+                              bool zt_scaled, hipStream_t st)
 {
     if (h.n_blocks == 0) return hipSuccess;
-    const size_t lds = (size_t)4 * kSkinnyRows * (h.max_r16 + 1) * sizeof(float);
+    const int n_split = skinny_splits(h, C);
+    const int n_stage_all = (int)((C + SK_BK - 1) / SK_BK);
+    const int per = (n_stage_all + n_split - 1) / n_split;
+    const size_t lds = (size_t)SK_NST * (SK_XT + h.max_r16 * SK_BK * 2);
     static size_t lds_allowed = 0;
     if (lds > lds_allowed) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny),
@@ -155,8 +282,12 @@ hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode,
         if (e != hipSuccess) return e;
         lds_allowed = lds;
     }
-    hipLaunchKernelGGL(k_skinny, dim3((unsigned)h.n_blocks), dim3(256), lds, st, mv, mode,
-                       static_cast<const uint16_t *>(S), C, static_cast<const uint16_t *>(at), hf,
+    hipLaunchKernelGGL(k_skinny, dim3((unsigned)h.n_blocks, (unsigned)n_split), dim3(256), lds, st, mv, mode,
+                       static_cast<const uint16_t *>(S), (int)C, static_cast<const uint16_t *>(at),
+                       static_cast<const uint16_t *>(zero), part, per);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_skinny_finish, dim3((unsigned)h.n_blocks, kSkinnyRows / 16), dim3(256), 0, st, mv, mode, part, n_split, hf,
                        static_cast<uint16_t *>(hb), static_cast<uint16_t *>(zt), zt_scaled ? 1 : 0);
     return hipGetLastError();
 }

@@ -102,11 +102,12 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-// One block per token block of kSkinnyRows rows: zt[j][t] = bf16(h[t][j]); rows j >= r and the
-// padding columns of the block are written as zero.
+// zt[j][t] = bf16(h[t][j]); rows j >= r and the padding tokens are written as zero.  Grid: (token
+// block of kSkinnyRows rows, slice of 16 rows inside it).
 __global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, uint16_t *zt)
 {
-    __shared__ float tile[kSkinnyRows][PLORA_MAX_RANK + 1];
+    constexpr int FR = 16;
+    __shared__ float tile[FR][PLORA_MAX_RANK + 1];
     const int blk = blockIdx.x;
     const int n_seg = mv.hdr->n_seg;
     int s = 0;
@@ -115,24 +116,24 @@ __global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, u
         if (g.adapter >= 0 && g.row1 > g.row0 && blk >= g.blk0) s = q;
     }
     const SegInfo g = mv.seg[s];
-    const int t0 = (blk - g.blk0) * kSkinnyRows;        // first token of the block inside the segment
-    const int len = g.row1 - g.row0;
-    const int nt = (len - t0 < kSkinnyRows) ? len - t0 : kSkinnyRows;
+    const int t0 = (blk - g.blk0) * kSkinnyRows + blockIdx.y * FR;   // first token of the slice inside the segment
+    if (t0 >= g.lp) return;
+    int nt = g.row1 - g.row0 - t0;
+    nt = nt < 0 ? 0 : (nt < FR ? nt : FR);
     const float *src = hf + g.h_off + (int64_t)t0 * g.r;
     for (int e = threadIdx.x; e < nt * g.r; e += 256) tile[e / g.r][e % g.r] = src[e];
     __syncthreads();
-    uint16_t *dst = zt + g.zt_off;
-    for (int e = threadIdx.x; e < g.r16 * kSkinnyRows; e += 256) {
-        const int j = e / kSkinnyRows, tt = e % kSkinnyRows;
-        if (t0 + tt < g.lp)
-            dst[(int64_t)j * g.lp + t0 + tt] = (j < g.r && tt < nt) ? f32_to_bf16_rne(tile[tt][j]) : (uint16_t)0;
+    uint16_t *dst = zt + g.zt_off + t0;
+    for (int e = threadIdx.x; e < g.r16 * FR; e += 256) {
+        const int j = e / FR, tt = e % FR;
+        dst[(int64_t)j * g.lp + tt] = (j < g.r && tt < nt) ? f32_to_bf16_rne(tile[tt][j]) : (uint16_t)0;
     }
 }
 
 hipError_t launch_h_to_zt(const MetaView &mv, const MetaHeader &h, const float *hf, void *zt, hipStream_t st)
 {
     if (h.n_blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_h_to_zt, dim3((unsigned)h.n_blocks), dim3(256), 0, st, mv, hf, static_cast<uint16_t *>(zt));
+    hipLaunchKernelGGL(k_h_to_zt, dim3((unsigned)h.n_blocks, kSkinnyRows / 16), dim3(256), 0, st, mv, hf, static_cast<uint16_t *>(zt));
     return hipGetLastError();
 }
 

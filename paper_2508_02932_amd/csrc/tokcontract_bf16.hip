@@ -6,10 +6,12 @@
 // against the small transposed bf16 factor zt[j][t] written by the skinny kernel.
 //
 // The token index is the slow index of the big matrix, so its MFMA operand needs a transpose; it
-// is staged HBM -> LDS as it lies in memory and read with the transposing LDS load
-// (ds_read_b64_tr_b16).  The rank stays whole in every tile; tiles are cut along the hidden
-// dimension (128 columns per workgroup) and the workgroup walks all tokens of the adapter, so no
-// partial sums ever leave the chip and the summation order is fixed.
+// is staged HBM -> LDS as it lies in memory (direct loads, three-stage ring) and read with the
+// transposing LDS load (ds_read_b64_tr_b16).  The rank stays whole in every tile; tiles are cut
+// along the hidden dimension (256 columns per workgroup) and a workgroup walks the tokens of one
+// adapter.  When that gives too few workgroups to fill the chip the token walk is split as well and
+// the fp32 partial tiles are summed, in a fixed order, by a small finishing kernel; otherwise the
+// result is written directly.  No atomics anywhere: the summation order is fixed.
 #include "plora_internal.h"
 
 namespace plora {
@@ -19,18 +21,24 @@ typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
-#define GLB_PTR(p) ((const __attribute__((address_space(1))) void *)(p))
 
-constexpr int TC_BC = 128;                 // columns of the big matrix per workgroup
-constexpr int TC_BT = 32;                  // tokens per stage (one MFMA K step)
-constexpr int TC_NST = 4;                  // LDS stages
-constexpr int TC_S_BYTES = TC_BT * TC_BC * 2;             // 8 KB  [32 t][128 c]
-constexpr int TC_Z_BYTES = PLORA_MAX_RANK * TC_BT * 2;    // 8 KB  [128 j][32 t]
-constexpr int TC_STAGE = TC_S_BYTES + TC_Z_BYTES;
-constexpr int TC_LDS = TC_NST * TC_STAGE;                 // 64 KB
+constexpr int TC_BC = 256;                 // columns of the big matrix per workgroup
+constexpr int TC_BT = 64;                  // tokens per stage (two MFMA K steps)
+constexpr int TC_NST = 3;                  // LDS ring stages
+constexpr int TC_S_BYTES = TC_BT * TC_BC * 2;             // 32 KB  [64 t][256 c]
+constexpr int TC_SL = TC_S_BYTES / 1024 / 4;              // big-matrix load instructions per wave per stage
+constexpr int TC_CB = TC_BC / 16 / 4;                     // 16-column MFMA blocks per wave
 constexpr int TC_NB = PLORA_MAX_RANK / 16;
 
-struct TokCursor { int seg; int t; };      // next stage to fetch: segment index, token offset inside it
+__device__ inline void tc_wait_vmcnt(int n)
+{
+#define W_(N) case N: __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14)); break;
+    switch (n) {
+        W_(0) W_(1) W_(2) W_(3) W_(4) W_(5) W_(6) W_(7) W_(8) W_(9) W_(10) W_(11) W_(12) W_(13) W_(14) W_(15) W_(16)
+    default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+    }
+#undef W_
+}
 
 __device__ inline int next_seg_of(const MetaView &mv, int from, int k)
 {
@@ -40,9 +48,12 @@ __device__ inline int next_seg_of(const MetaView &mv, int from, int k)
     return n;
 }
 
+// grid (column tiles, adapters, token splits).  part != nullptr: write the fp32 partial tile
+// [r16][C] of this split instead of the final result.
 template <bool WANT_DA>
 __global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__restrict__ S, int C,
-                                             const uint16_t *__restrict__ zt, const uint16_t *__restrict__ zero)
+                                             const uint16_t *__restrict__ zt, const uint16_t *__restrict__ zero,
+                                             float *__restrict__ part, int r16_total)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int k = blockIdx.y;
@@ -50,101 +61,121 @@ __global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__res
     const int c0 = blockIdx.x * TC_BC;
     const int n_seg = mv.hdr->n_seg;
     const int nb = a.r16 / 16;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
+    const int stage_bytes = TC_S_BYTES + mv.hdr->max_r16 * TC_BT * 2;
 
-    int n_steps = 0;
+    // steps (64 tokens each) of this adapter, and the slice of them that belongs to this split
+    int n_steps_all = 0;
     for (int s = next_seg_of(mv, 0, k); s < n_seg; s = next_seg_of(mv, s + 1, k))
-        n_steps += (mv.seg[s].row1 - mv.seg[s].row0 + TC_BT - 1) / TC_BT;
+        n_steps_all += (mv.seg[s].row1 - mv.seg[s].row0 + TC_BT - 1) / TC_BT;
+    const int per = (n_steps_all + gridDim.z - 1) / gridDim.z;
+    const int step0 = blockIdx.z * per;
+    int n_steps = n_steps_all - step0;
+    n_steps = n_steps < per ? n_steps : per;
+    if (n_steps < 0) n_steps = 0;
 
-    // ---- loader.  Big-matrix tile [32 t][16 chunks]: instruction q covers token rows 4q..4q+3, lane ->
-    // (row 4q + lane/16, slot lane%16), slot c' of row u holds chunk c' ^ (2*(u&3) + 8*((u>>3)&1)).
-    // Small-factor tile [128 j][4 chunks]: instruction q covers rows 16q..16q+15, lane -> (row 16q +
-    // lane/4, slot lane%4), slot c' of row u holds chunk c' ^ ((u>>2)&3).  Every wave issues exactly
-    // 2 + 2 loads per stage (rows of the small factor beyond r16 fetch zeros) so that the number of
-    // loads in flight per stage is a constant the wait instruction can name.
-    TokCursor cur;
-    cur.seg = next_seg_of(mv, 0, k);
-    cur.t = 0;
-    auto issue = [&](int stage) {
-        char *ss = lds + stage * TC_STAGE;
-        char *sz = ss + TC_S_BYTES;
-        const SegInfo g = mv.seg[cur.seg];
+    // cursor of the next stage to fetch: segment index and token offset inside it
+    int cur_seg = next_seg_of(mv, 0, k), cur_t = 0;
+    for (int skip = step0; skip > 0 && cur_seg < n_seg;) {
+        const int st_here = (mv.seg[cur_seg].row1 - mv.seg[cur_seg].row0 + TC_BT - 1) / TC_BT;
+        if (skip >= st_here) { skip -= st_here; cur_seg = next_seg_of(mv, cur_seg + 1, k); }
+        else { cur_t = skip * TC_BT; skip = 0; }
+    }
+
+    // ---- loader.  Big-matrix tile [64 t][32 chunks] (512-byte rows): instruction q covers token rows
+    // 2q, 2q+1, lane -> (row 2q + lane/32, slot lane%32), slot c' of row u holds chunk
+    // c' ^ (4*(u&3) + 2*((u>>3)&1)); wave w issues q = w, w+4, ..., w+28.  Small-factor tile
+    // [r16 j][8 chunks]: instruction q covers rows 8q..8q+7, lane -> (row 8q + lane/8, slot lane%8), slot c'
+    // of row u holds chunk c' ^ ((u>>1)&7); wave w issues q = w, w+4, ... below r16/8.
+    const int nzi = a.r16 / 8;
+    const int my_z = (nzi > wave) ? (nzi - wave + 3) / 4 : 0;
+    const int lps = TC_SL + my_z;
+    auto load16 = [&](const uint16_t *gp, uint32_t dst) {
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gp), "s"(dst));
+    };
+    auto issue = [&](int slot) {
+        const uint32_t base = lds_base + slot * stage_bytes;
+        const int sidx = __builtin_amdgcn_readfirstlane(cur_seg);
+        const int tbase = __builtin_amdgcn_readfirstlane(cur_t);
+        const SegInfo g = mv.seg[sidx];
         const int len = g.row1 - g.row0;
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
+        for (int jj = 0; jj < TC_SL; ++jj) {
             const int q = wave + 4 * jj;
-            const int u = q * 4 + (lane >> 4);
-            int chunk = (lane & 15) ^ (2 * (u & 3) + 8 * ((u >> 3) & 1));
+            const int u = q * 2 + (lane >> 5);
+            const int chunk = (lane & 31) ^ (4 * (u & 3) + 2 * ((u >> 3) & 1));
             int c = c0 + chunk * 8;
             c = c < C ? c : C - 8;                                  // columns past the end only feed outputs that are not stored
-            const int t = cur.t + u;
+            const int t = tbase + u;
             const uint16_t *p = (t < len) ? S + (int64_t)(g.row0 + t) * C + c : zero;
-            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(void, ss + q * 1024), 16, 0, 0);
+            load16(p, base + q * 1024);
         }
 #pragma unroll
-        for (int jj = 0; jj < 2; ++jj) {
-            const int q = wave + 4 * jj;
-            const int u = q * 16 + (lane >> 2);
-            const int chunk = (lane & 3) ^ ((u >> 2) & 3);
-            const uint16_t *p = (u < g.r16) ? zt + g.zt_off + (int64_t)u * g.lp + cur.t + chunk * 8 : zero + lane * 8;
-            __builtin_amdgcn_global_load_lds(GLB_PTR(p), LDS_PTR(void, sz + q * 1024), 16, 0, 0);
+        for (int jj = 0; jj < 4; ++jj) {
+            if (jj < my_z) {
+                const int q = wave + 4 * jj;
+                const int u = q * 8 + (lane >> 3);
+                const int chunk = (lane & 7) ^ ((u >> 1) & 7);
+                load16(zt + g.zt_off + (int64_t)u * g.lp + tbase + chunk * 8, base + TC_S_BYTES + q * 1024);
+            }
         }
-        cur.t += TC_BT;
-        if (cur.t >= len) { cur.seg = next_seg_of(mv, cur.seg + 1, k); cur.t = 0; }
+        cur_t = tbase + TC_BT;
+        if (cur_t >= len) { cur_seg = next_seg_of(mv, sidx + 1, k); cur_t = 0; }
     };
 
-    // ---- MFMA operands.  Wave w owns columns 32w..32w+31 (two 16-column blocks) and every rank block.
+    // ---- MFMA operands.  Wave w owns columns 64w..64w+63 (four 16-column blocks) and every rank block.
     // Transposing read of the big-matrix operand: the 16 lanes of group kg fetch the 4(t) x 16(c) block
-    // at tokens kg*8 (+4 for the second read), 8 bytes each; lane i then holds column i.
+    // at tokens 32*ks + 8*kg (+4 for the second read), 8 bytes each; lane i then holds column i.
     const int i16 = lane & 15, kg = lane >> 4;
-    int soff[2];
+    int soff[TC_CB];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int u = kg * 8 + (i16 >> 2);                            // token row fetched by this lane (first read)
-        const int cl = wave * 32 + cb * 16 + (i16 & 3) * 4;           // first column fetched by this lane
-        soff[cb] = u * 256 + ((((cl >> 3) ^ (2 * (u & 3) + 8 * ((u >> 3) & 1))) * 16) + (cl & 7) * 2);
+    for (int cb = 0; cb < TC_CB; ++cb) {
+        const int u = kg * 8 + (i16 >> 2);                            // token row fetched by this lane (first read, ks = 0)
+        const int cl = wave * (TC_CB * 16) + cb * 16 + (i16 & 3) * 4; // first column fetched by this lane
+        soff[cb] = u * (TC_BC * 2) + ((((cl >> 3) ^ (4 * (u & 3) + 2 * ((u >> 3) & 1))) * 16) + (cl & 7) * 2);
     }
-    // second read: token row u+4 -> (u&3) and (u>>3)&1 unchanged, plain +4*256
+    // second read: token row u+4, next K step: u+32 -> (u&3) and (u>>3)&1 unchanged, plain adds
     int zoff[TC_NB];
 #pragma unroll
     for (int b = 0; b < TC_NB; ++b) {
         const int u = b * 16 + i16;                                   // rank row j
-        zoff[b] = u * 64 + ((kg ^ ((u >> 2) & 3)) * 16);
+        zoff[b] = TC_S_BYTES + u * 128 + ((kg ^ ((u >> 1) & 7)) * 16);   // chunk 4*ks + kg: ks XORs in as 64 bytes
     }
 
-    f32x4 acc[2][TC_NB];
+    f32x4 acc[TC_CB][TC_NB];
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb)
+    for (int cb = 0; cb < TC_CB; ++cb)
 #pragma unroll
         for (int b = 0; b < TC_NB; ++b) acc[cb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int p = 0; p < TC_NST - 1; ++p) {
+    for (int p = 0; p < TC_NST - 1; ++p)
         if (p < n_steps) issue(p);
-    }
     for (int it = 0; it < n_steps; ++it) {
-        // loads of the stages it+1 .. it+NST-2 may stay in flight: 4 instructions each
         const int ahead = (n_steps - 1 - it < TC_NST - 2) ? n_steps - 1 - it : TC_NST - 2;
-        if (ahead >= 2) __builtin_amdgcn_s_waitcnt(0x0f70 | 8);
-        else if (ahead == 1) __builtin_amdgcn_s_waitcnt(0x0f70 | 4);
-        else __builtin_amdgcn_s_waitcnt(0x0f70);
-        __syncthreads();
+        tc_wait_vmcnt(ahead * lps);
+        __builtin_amdgcn_s_barrier();
         if (it + TC_NST - 1 < n_steps) issue((it + TC_NST - 1) % TC_NST);
-        const char *ss = lds + (it % TC_NST) * TC_STAGE;
-        const char *sz = ss + TC_S_BYTES;
-        bf16x8 sf[2];
+        const char *sb = lds + (it % TC_NST) * stage_bytes;
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-            bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, ss + soff[cb]));
-            bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, ss + soff[cb] + 4 * 256));
-            sf[cb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-        }
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 sf[TC_CB];
 #pragma unroll
-        for (int b = 0; b < TC_NB; ++b) {
-            if (b < nb) {
-                const bf16x8 zf = *LDS_PTR(const bf16x8, sz + zoff[b]);
+            for (int cb = 0; cb < TC_CB; ++cb) {
+                const char *p = sb + soff[cb] + ks * 32 * (TC_BC * 2);
+                bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p));
+                bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p + 4 * (TC_BC * 2)));
+                sf[cb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            }
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
-                    acc[cb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf[cb], zf, acc[cb][b], 0, 0, 0);
+            for (int b = 0; b < TC_NB; ++b) {
+                if (b < nb) {
+                    const bf16x8 zf = *LDS_PTR(const bf16x8, sb + (zoff[b] ^ (ks * 64)));
+#pragma unroll
+                    for (int cb = 0; cb < TC_CB; ++cb)
+                        acc[cb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf[cb], zf, acc[cb][b], 0, 0, 0);
+                }
             }
         }
     }
@@ -152,45 +183,94 @@ __global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__res
     // ---- epilogue.  Lane holds rank column j = 16b + i16 and big-matrix columns c = cbase + 4*kg + i.
     const float mult = WANT_DA ? 1.f : a.scale;
 #pragma unroll
-    for (int cb = 0; cb < 2; ++cb) {
-        const int c = c0 + wave * 32 + cb * 16 + kg * 4;
+    for (int cb = 0; cb < TC_CB; ++cb) {
+        const int c = c0 + wave * (TC_CB * 16) + cb * 16 + kg * 4;
 #pragma unroll
         for (int b = 0; b < TC_NB; ++b) {
             const int j = b * 16 + i16;
-            if (b < nb && j < a.r && c < C) {
-                if (WANT_DA) {
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) a.dA[(int64_t)(c + i) * a.r + j] = acc[cb][b][i];
-                } else {
+            if (b < nb && c < C) {
+                if (part) {
                     float4 v;
-                    v.x = mult * acc[cb][b][0]; v.y = mult * acc[cb][b][1];
-                    v.z = mult * acc[cb][b][2]; v.w = mult * acc[cb][b][3];
-                    *reinterpret_cast<float4 *>(a.dB + (int64_t)j * C + c) = v;
+                    v.x = acc[cb][b][0]; v.y = acc[cb][b][1]; v.z = acc[cb][b][2]; v.w = acc[cb][b][3];
+                    *reinterpret_cast<float4 *>(part + ((int64_t)blockIdx.z * r16_total + a.r16_off + j) * C + c) = v;
+                } else if (j < a.r) {
+                    if (WANT_DA) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) a.dA[(int64_t)(c + i) * a.r + j] = acc[cb][b][i];
+                    } else {
+                        float4 v;
+                        v.x = mult * acc[cb][b][0]; v.y = mult * acc[cb][b][1];
+                        v.z = mult * acc[cb][b][2]; v.w = mult * acc[cb][b][3];
+                        *reinterpret_cast<float4 *>(a.dB + (int64_t)j * C + c) = v;
+                    }
                 }
             }
         }
     }
 }
 
+// Sums the partial tiles [split][r16 rows][C] in split order and writes dA_k[c][j] or scale_k-scaled
+// dB_k[j][c].  grid (C / 256, rank rows of all adapters); one output element per thread.
+template <bool WANT_DA>
+__global__ void __launch_bounds__(256) k_tokc_finish(MetaView mv, const float *__restrict__ part, int C, int n_split,
+                                                    int r16_total)
+{
+    const int row = blockIdx.y;                      // row of the concatenated [r16_total][C] partial tile
+    const int n_ad = mv.hdr->n_adapters;
+    int k = 0;
+    for (int q = 0; q < n_ad; ++q)
+        if (row >= mv.ad[q].r16_off) k = q;
+    const AdapterInfo a = mv.ad[k];
+    const int j = row - a.r16_off;
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (j >= a.r || c >= C) return;
+    float v[kTokMaxSplits];
+#pragma unroll
+    for (int sp = 0; sp < kTokMaxSplits; ++sp)
+        v[sp] = (sp < n_split) ? part[((int64_t)sp * r16_total + row) * C + c] : 0.f;
+    float sum = v[0];
+#pragma unroll
+    for (int sp = 1; sp < kTokMaxSplits; ++sp) sum += v[sp];
+    if (WANT_DA) a.dA[(int64_t)c * a.r + j] = sum;
+    else a.dB[(int64_t)j * C + c] = a.scale * sum;
+}
+
+int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters)
+{
+    if (n_active_adapters <= 0) return 1;
+    const int64_t wgs = (C + TC_BC - 1) / TC_BC * n_active_adapters;
+    int want = (int)((768 + wgs - 1) / wgs);
+    int cap = (int)(h.T / TC_BT / n_active_adapters / 4);     // keep about four stages per split at least
+    if (cap < 1) cap = 1;
+    if (want > cap) want = cap;
+    if (want > kTokMaxSplits) want = kTokMaxSplits;
+    return want < 1 ? 1 : want;
+}
+
 hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool want_dA, const void *S,
-                                   int64_t C, const void *zt, const void *zero, hipStream_t st)
+                                   int64_t C, const void *zt, const void *zero, float *part, int n_split,
+                                   int r16_total, hipStream_t st)
 {
     if (h.n_adapters == 0) return hipSuccess;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_tokc<true>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, TC_LDS);
-        if (e == hipSuccess)
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_tokc<false>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, TC_LDS);
+    const size_t lds = (size_t)TC_NST * (TC_S_BYTES + (h.max_r16 > 0 ? h.max_r16 : 16) * TC_BT * 2);
+    static size_t allowed[2] = {0, 0};
+    if (lds > allowed[want_dA ? 1 : 0]) {
+        const void *f = want_dA ? reinterpret_cast<const void *>(k_tokc<true>) : reinterpret_cast<const void *>(k_tokc<false>);
+        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
-        attr_done = true;
+        allowed[want_dA ? 1 : 0] = lds;
     }
-    const dim3 grid((unsigned)((C + TC_BC - 1) / TC_BC), (unsigned)h.n_adapters);
+    float *p = n_split > 1 ? part : nullptr;
+    const dim3 grid((unsigned)((C + TC_BC - 1) / TC_BC), (unsigned)h.n_adapters, (unsigned)n_split);
     const uint16_t *s16 = static_cast<const uint16_t *>(S), *z16 = static_cast<const uint16_t *>(zt);
     const uint16_t *zero16 = static_cast<const uint16_t *>(zero);
-    if (want_dA) hipLaunchKernelGGL(k_tokc<true>, grid, dim3(256), TC_LDS, st, mv, s16, (int)C, z16, zero16);
-    else hipLaunchKernelGGL(k_tokc<false>, grid, dim3(256), TC_LDS, st, mv, s16, (int)C, z16, zero16);
+    if (want_dA) hipLaunchKernelGGL(k_tokc<true>, grid, dim3(256), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total);
+    else hipLaunchKernelGGL(k_tokc<false>, grid, dim3(256), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n_split <= 1) return e;
+    const dim3 g2((unsigned)((C + 255) / 256), (unsigned)r16_total);
+    if (want_dA) hipLaunchKernelGGL(k_tokc_finish<true>, g2, dim3(256), 0, st, mv, part, (int)C, n_split, r16_total);
+    else hipLaunchKernelGGL(k_tokc_finish<false>, g2, dim3(256), 0, st, mv, part, (int)C, n_split, r16_total);
     return hipGetLastError();
 }
 

@@ -29,9 +29,12 @@ def round_to_bf16(a: np.ndarray) -> np.ndarray:
     Finite inputs only."""
     a = np.ascontiguousarray(a, dtype=np.float32)
     u = a.view(np.uint32)
-    bias = ((u >> np.uint32(16)) & np.uint32(1)) + np.uint32(0x7FFF)
-    out = ((u + bias) & np.uint32(0xFFFF0000)).view(np.float32)
-    return out
+    w = u >> np.uint32(16)          # in-place steps below keep large inputs to one temporary
+    w &= np.uint32(1)
+    w += np.uint32(0x7FFF)
+    w += u
+    w &= np.uint32(0xFFFF0000)
+    return w.view(np.float32)
 
 
 def bf16_bits(a: np.ndarray) -> np.ndarray:
