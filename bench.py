@@ -33,6 +33,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default: the headline one)")
     ap.add_argument("--linear", type=int, default=0, help="which linear of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy a few times (reference for the rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE counters when profiling this script)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -62,6 +65,14 @@ def main():
     def step():
         plora.plora_linear_fwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.y, dp.h, dp.ws)
         plora.plora_linear_bwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.dy, dp.h, dp.dx, dp.dA, dp.dB, dp.ws)
+
+    if args.calib_copy:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
@@ -110,10 +121,19 @@ def main():
         kernels["pack"] = {"ms": round(kern["pack"], 4)}
     # when the saved activation is handed to backward, class "shrink" of the last call is the
     # conversion kernel; the forward shrink is what the roofline entry should describe
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_config{args.config}_linear{args.linear}.txt")
+    if os.path.exists(tpath):
+        # committed summary of two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this script, already
+        # scaled by the copy-kernel calibration; line format: "gemm_fwd <bytes per launch>"
+        for line in open(tpath):
+            parts = line.split()
+            if len(parts) >= 2 and parts[0] == "gemm_fwd":
+                traffic = float(parts[1])
     dom = kernels.get("gemm_fwd", {})
     roofline = {"kernel": "k_gemm<forward> (x W with fused scale*h*B_k)", "bound": "mfma",
                 "achieved": dom.get("achieved"), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": dom.get("frac"), "traffic": None,
+                "frac": dom.get("frac"), "traffic": traffic,
                 "avg_launch_ms": dom.get("ms")}
 
     cpu = None
