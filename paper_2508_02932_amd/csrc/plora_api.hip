@@ -4,6 +4,7 @@
 #include "plora_internal.h"
 
 #include <cstring>
+#include <algorithm>
 #include <vector>
 
 namespace plora {
@@ -92,6 +93,16 @@ static void build_meta(const plora_desc *d, HostMeta &m)
             if (m.seg[s].adapter >= 0 && m.seg[s].row1 > m.seg[s].row0) seen[m.seg[s].adapter] = 1;
         m.n_active = 0;
         for (char c : seen) m.n_active += c;
+    }
+    {
+        // the weight-gradient kernels hand out adapters longest first, so the last workgroups are short
+        std::vector<int64_t> tokens(d->n_adapters, 0);
+        for (int32_t s = 0; s < d->n_seg; ++s)
+            if (m.seg[s].adapter >= 0) tokens[m.seg[s].adapter] += m.seg[s].row1 - m.seg[s].row0;
+        std::vector<int32_t> order(d->n_adapters);
+        for (int32_t k = 0; k < d->n_adapters; ++k) order[k] = k;
+        std::stable_sort(order.begin(), order.end(), [&](int32_t a, int32_t b) { return tokens[a] > tokens[b]; });
+        for (int32_t k = 0; k < d->n_adapters; ++k) m.ad[k].by_tokens = order[k];
     }
     m.split_dA = tokc_splits(m.hdr, d->d_in, m.n_active);
     m.split_dB = tokc_splits(m.hdr, d->d_out, m.n_active);

@@ -43,7 +43,7 @@ struct AdapterInfo {
     int64_t at_off;       // element offset of A^T  [r16][d_in]  in the packed-A^T buffer
     int64_t ap_off;       // element offset of A    [d_in][rp]   in the padded-A buffer
     int32_t r16_off;      // sum of r16 over the adapters before this one (row offset in dA / dB partial tiles)
-    int32_t pad_;
+    int32_t by_tokens;    // entry i: the adapter with the i-th largest token count (ties by index)
 };
 
 struct MetaHeader {

@@ -6,13 +6,18 @@
 // against the small transposed bf16 factor zt[j][t] written by the skinny kernel.
 //
 // The token index is the slow index of the big matrix, so its MFMA operand needs a transpose; it
-// is staged HBM -> LDS as it lies in memory (direct loads, three-stage ring) and read with the
-// transposing LDS load (ds_read_b64_tr_b16).  The rank stays whole in every tile; tiles are cut
-// along the hidden dimension (256 columns per workgroup) and a workgroup walks the tokens of one
-// adapter.  When that gives too few workgroups to fill the chip the token walk is split as well and
+// is staged HBM -> LDS as it lies in memory (direct loads into a ring of stages that fills the LDS)
+// and read with the transposing LDS load (ds_read_b64_tr_b16).  The rank stays whole in every tile;
+// tiles are cut along the hidden dimension (256 columns per workgroup of eight waves, 32 columns
+// per wave) and a workgroup walks the tokens of one adapter, longest adapters first.  The MFMA code
+// is specialised per number of 16-wide rank blocks so that every LDS read of a stage is in flight
+// before the first MFMA.  Nothing in the loop may spill: a scratch reload waits on the same counter
+// as the direct loads and would drain the ring.
+// When that gives too few workgroups to fill the chip the token walk is split as well and
 // the fp32 partial tiles are summed, in a fixed order, by a small finishing kernel; otherwise the
 // result is written directly.  No atomics anywhere: the summation order is fixed.
 #include "plora_internal.h"
+#include <type_traits>
 
 namespace plora {
 
@@ -23,19 +28,28 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 
 constexpr int TC_BC = 256;                 // columns of the big matrix per workgroup
-constexpr int TC_BT = 64;                  // tokens per stage (two MFMA K steps)
-constexpr int TC_NST = 3;                  // LDS ring stages
-constexpr int TC_S_BYTES = TC_BT * TC_BC * 2;             // 32 KB  [64 t][256 c]
-constexpr int TC_SL = TC_S_BYTES / 1024 / 4;              // big-matrix load instructions per wave per stage
-constexpr int TC_CB = TC_BC / 16 / 4;                     // 16-column MFMA blocks per wave
+constexpr int TC_BT = 64;                  // tokens per stage (TC_BT / 32 MFMA K steps)
+constexpr int TC_MAX_NST = 8;              // LDS ring stages: as many as fit in the 160 KB of a compute unit, at most this
+constexpr int TC_LDS_BYTES = 160 * 1024;
+constexpr int TC_S_BYTES = TC_BT * TC_BC * 2;             // [TC_BT t][256 c]
+constexpr int TC_NW = 8;                                  // waves per workgroup
+constexpr int TC_SL = TC_S_BYTES / 1024 / TC_NW;          // big-matrix load instructions per wave per stage
+constexpr int TC_CB = TC_BC / 16 / TC_NW;                 // 16-column MFMA blocks per wave
 constexpr int TC_NB = PLORA_MAX_RANK / 16;
+constexpr int TC_KS = TC_BT / 32;                         // MFMA K steps per stage
+constexpr int TC_ZC = TC_BT / 8;                          // 16-byte chunks per small-factor row
+constexpr int TC_ZR = 64 / TC_ZC;                         // small-factor rows per load instruction
+constexpr int TC_ZSH = TC_ZC == 4 ? 2 : 1;                // rows that share a 256-byte LDS line: 4 or 2
+static_assert(TC_BT == 32 || TC_BT == 64, "");
 
 __device__ inline void tc_wait_vmcnt(int n)
 {
 #define W_(N) case N: __builtin_amdgcn_s_waitcnt(0x0f70 | (N & 15) | ((N >> 4) << 14)); break;
     switch (n) {
         W_(0) W_(1) W_(2) W_(3) W_(4) W_(5) W_(6) W_(7) W_(8) W_(9) W_(10) W_(11) W_(12) W_(13) W_(14) W_(15) W_(16)
-    default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+        W_(17) W_(18) W_(19) W_(20) W_(21) W_(22) W_(23) W_(24) W_(25) W_(26) W_(27) W_(28) W_(29) W_(30) W_(31) W_(32)
+        W_(33) W_(34) W_(35) W_(36) W_(37) W_(38) W_(39) W_(40) W_(41) W_(42) W_(43) W_(44) W_(45) W_(46) W_(47) W_(48)
+    default: __builtin_amdgcn_s_waitcnt(0x0f70); break;    // never reached: at most (TC_MAX_NST - 2) * 6 loads stay in flight
     }
 #undef W_
 }
@@ -51,12 +65,12 @@ __device__ inline int next_seg_of(const MetaView &mv, int from, int k)
 // grid (column tiles, adapters, token splits).  part != nullptr: write the fp32 partial tile
 // [r16][C] of this split instead of the final result.
 template <bool WANT_DA>
-__global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__restrict__ S, int C,
+__global__ void __launch_bounds__(64 * TC_NW) k_tokc(MetaView mv, const uint16_t *__restrict__ S, int C,
                                              const uint16_t *__restrict__ zt, const uint16_t *__restrict__ zero,
-                                             float *__restrict__ part, int r16_total)
+                                             float *__restrict__ part, int r16_total, int nst)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const int k = blockIdx.y;
+    const int k = mv.ad[blockIdx.y].by_tokens;       // longest adapters first
     const AdapterInfo a = mv.ad[k];
     const int c0 = blockIdx.x * TC_BC;
     const int n_seg = mv.hdr->n_seg;
@@ -66,7 +80,7 @@ __global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__res
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
     const int stage_bytes = TC_S_BYTES + mv.hdr->max_r16 * TC_BT * 2;
 
-    // steps (64 tokens each) of this adapter, and the slice of them that belongs to this split
+    // steps (TC_BT tokens each) of this adapter, and the slice of them that belongs to this split
     int n_steps_all = 0;
     for (int s = next_seg_of(mv, 0, k); s < n_seg; s = next_seg_of(mv, s + 1, k))
         n_steps_all += (mv.seg[s].row1 - mv.seg[s].row0 + TC_BT - 1) / TC_BT;
@@ -76,73 +90,78 @@ __global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__res
     n_steps = n_steps < per ? n_steps : per;
     if (n_steps < 0) n_steps = 0;
 
-    // cursor of the next stage to fetch: segment index and token offset inside it
+    // cursor of the next stage to fetch: segment index, token offset inside it, and the fields of that
+    // segment that the loader needs (kept in registers so that the load issue right behind the barrier
+    // does not wait for a metadata fetch)
     int cur_seg = next_seg_of(mv, 0, k), cur_t = 0;
     for (int skip = step0; skip > 0 && cur_seg < n_seg;) {
         const int st_here = (mv.seg[cur_seg].row1 - mv.seg[cur_seg].row0 + TC_BT - 1) / TC_BT;
         if (skip >= st_here) { skip -= st_here; cur_seg = next_seg_of(mv, cur_seg + 1, k); }
         else { cur_t = skip * TC_BT; skip = 0; }
     }
+    int seg_row0 = 0, seg_len = 0, seg_lp = 0;
+    int64_t seg_zt = 0;
+    auto load_desc = [&]() {
+        if (cur_seg < n_seg) {
+            const SegInfo g = mv.seg[cur_seg];
+            seg_row0 = g.row0; seg_len = g.row1 - g.row0; seg_lp = g.lp; seg_zt = g.zt_off;
+        }
+    };
+    load_desc();
 
-    // ---- loader.  Big-matrix tile [64 t][32 chunks] (512-byte rows): instruction q covers token rows
+    // ---- loader.  Big-matrix tile [TC_BT t][32 chunks] (512-byte rows): instruction q covers token rows
     // 2q, 2q+1, lane -> (row 2q + lane/32, slot lane%32), slot c' of row u holds chunk
-    // c' ^ (4*(u&3) + 2*((u>>3)&1)); wave w issues q = w, w+4, ..., w+28.  Small-factor tile
-    // [r16 j][8 chunks]: instruction q covers rows 8q..8q+7, lane -> (row 8q + lane/8, slot lane%8), slot c'
-    // of row u holds chunk c' ^ ((u>>1)&7); wave w issues q = w, w+4, ... below r16/8.
-    const int nzi = a.r16 / 8;
-    const int my_z = (nzi > wave) ? (nzi - wave + 3) / 4 : 0;
+    // c' ^ (4*(u&3) + 2*((u>>3)&1)); wave w issues q = w, w+8, ...  Small-factor tile [r16 j][TC_ZC chunks]:
+    // instruction q covers rows TC_ZR q.., lane -> (row TC_ZR q + lane/TC_ZC, slot lane%TC_ZC), slot c' of
+    // row u holds chunk c' ^ ((u >> TC_ZSH) & (TC_ZC-1)); wave w issues q = w, w+8 below r16/TC_ZR.
+    const int nzi = a.r16 / TC_ZR;
+    const int my_z = (nzi > wave) ? (nzi - wave + TC_NW - 1) / TC_NW : 0;
     const int lps = TC_SL + my_z;
     auto load16 = [&](const uint16_t *gp, uint32_t dst) {
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gp), "s"(dst));
     };
     auto issue = [&](int slot) {
         const uint32_t base = lds_base + slot * stage_bytes;
-        const int sidx = __builtin_amdgcn_readfirstlane(cur_seg);
         const int tbase = __builtin_amdgcn_readfirstlane(cur_t);
-        const SegInfo g = mv.seg[sidx];
-        const int len = g.row1 - g.row0;
 #pragma unroll
         for (int jj = 0; jj < TC_SL; ++jj) {
-            const int q = wave + 4 * jj;
+            const int q = wave + TC_NW * jj;
             const int u = q * 2 + (lane >> 5);
             const int chunk = (lane & 31) ^ (4 * (u & 3) + 2 * ((u >> 3) & 1));
             int c = c0 + chunk * 8;
             c = c < C ? c : C - 8;                                  // columns past the end only feed outputs that are not stored
             const int t = tbase + u;
-            const uint16_t *p = (t < len) ? S + (int64_t)(g.row0 + t) * C + c : zero;
+            const uint16_t *p = (t < seg_len) ? S + (int64_t)(seg_row0 + t) * C + c : zero;
             load16(p, base + q * 1024);
         }
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < 16 / TC_ZR / (TC_NW / 8); ++jj) {
             if (jj < my_z) {
-                const int q = wave + 4 * jj;
-                const int u = q * 8 + (lane >> 3);
-                const int chunk = (lane & 7) ^ ((u >> 1) & 7);
-                load16(zt + g.zt_off + (int64_t)u * g.lp + tbase + chunk * 8, base + TC_S_BYTES + q * 1024);
+                const int q = wave + TC_NW * jj;
+                const int u = q * TC_ZR + lane / TC_ZC;
+                const int chunk = (lane % TC_ZC) ^ ((u >> TC_ZSH) & (TC_ZC - 1));
+                load16(zt + seg_zt + (int64_t)u * seg_lp + tbase + chunk * 8, base + TC_S_BYTES + q * 1024);
             }
         }
         cur_t = tbase + TC_BT;
-        if (cur_t >= len) { cur_seg = next_seg_of(mv, sidx + 1, k); cur_t = 0; }
+        if (cur_t >= seg_len) { cur_seg = next_seg_of(mv, cur_seg + 1, k); cur_t = 0; load_desc(); }
     };
 
-    // ---- MFMA operands.  Wave w owns columns 64w..64w+63 (four 16-column blocks) and every rank block.
+    // ---- MFMA operands.  Wave w owns columns 32w..32w+31 (two 16-column blocks) and every rank block.
     // Transposing read of the big-matrix operand: the 16 lanes of group kg fetch the 4(t) x 16(c) block
     // at tokens 32*ks + 8*kg (+4 for the second read), 8 bytes each; lane i then holds column i.
     const int i16 = lane & 15, kg = lane >> 4;
     int soff[TC_CB];
 #pragma unroll
     for (int cb = 0; cb < TC_CB; ++cb) {
-        const int u = kg * 8 + (i16 >> 2);                            // token row fetched by this lane (first read, ks = 0)
+        const int u = kg * 8 + (i16 >> 2);                            // token row fetched by this lane (first read)
         const int cl = wave * (TC_CB * 16) + cb * 16 + (i16 & 3) * 4; // first column fetched by this lane
         soff[cb] = u * (TC_BC * 2) + ((((cl >> 3) ^ (4 * (u & 3) + 2 * ((u >> 3) & 1))) * 16) + (cl & 7) * 2);
     }
-    // second read: token row u+4, next K step: u+32 -> (u&3) and (u>>3)&1 unchanged, plain adds
-    int zoff[TC_NB];
-#pragma unroll
-    for (int b = 0; b < TC_NB; ++b) {
-        const int u = b * 16 + i16;                                   // rank row j
-        zoff[b] = TC_S_BYTES + u * 128 + ((kg ^ ((u >> 1) & 7)) * 16);   // chunk 4*ks + kg: ks XORs in as 64 bytes
-    }
+    // second read (token row u+4) and later K steps (u+32): (u&3) and (u>>3)&1 unchanged, plain adds
+    // small-factor operand: rank row j = 16b + i16, chunk 4*ks + kg; the swizzle term only depends on
+    // i16, so block b sits 16 rows behind block b-1 and K step ks flips one offset bit
+    const int zoff0 = TC_S_BYTES + i16 * (TC_BT * 2) + ((kg ^ ((i16 >> TC_ZSH) & (TC_ZC - 1))) * 16);
 
     f32x4 acc[TC_CB][TC_NB];
 #pragma unroll
@@ -150,17 +169,11 @@ __global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__res
 #pragma unroll
         for (int b = 0; b < TC_NB; ++b) acc[cb][b] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int p = 0; p < TC_NST - 1; ++p)
-        if (p < n_steps) issue(p);
-    for (int it = 0; it < n_steps; ++it) {
-        const int ahead = (n_steps - 1 - it < TC_NST - 2) ? n_steps - 1 - it : TC_NST - 2;
-        tc_wait_vmcnt(ahead * lps);
-        __builtin_amdgcn_s_barrier();
-        if (it + TC_NST - 1 < n_steps) issue((it + TC_NST - 1) % TC_NST);
-        const char *sb = lds + (it % TC_NST) * stage_bytes;
+    auto compute = [&](auto nbc, const char *sb) {
+        constexpr int NBC = decltype(nbc)::value;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            bf16x8 sf[TC_CB];
+        for (int ks = 0; ks < TC_KS; ++ks) {
+            bf16x8 sf[TC_CB], zf[NBC];
 #pragma unroll
             for (int cb = 0; cb < TC_CB; ++cb) {
                 const char *p = sb + soff[cb] + ks * 32 * (TC_BC * 2);
@@ -169,14 +182,38 @@ __global__ void __launch_bounds__(256) k_tokc(MetaView mv, const uint16_t *__res
                 sf[cb] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
             }
 #pragma unroll
-            for (int b = 0; b < TC_NB; ++b) {
-                if (b < nb) {
-                    const bf16x8 zf = *LDS_PTR(const bf16x8, sb + (zoff[b] ^ (ks * 64)));
+            for (int b = 0; b < NBC; ++b) zf[b] = *LDS_PTR(const bf16x8, sb + (zoff0 ^ (ks * 64)) + b * 16 * (TC_BT * 2));
 #pragma unroll
-                    for (int cb = 0; cb < TC_CB; ++cb)
-                        acc[cb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf[cb], zf, acc[cb][b], 0, 0, 0);
-                }
-            }
+            for (int b = 0; b < NBC; ++b)
+#pragma unroll
+                for (int cb = 0; cb < TC_CB; ++cb)
+                    acc[cb][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(sf[cb], zf[b], acc[cb][b], 0, 0, 0);
+        }
+    };
+
+    // ring of nst stages: stage `it` lives in slot it % nst; nst - 1 stages are in flight ahead of the reader
+    for (int p = 0; p < nst - 1; ++p)
+        if (p < n_steps) issue(p);
+    int rd_slot = 0, wr_slot = nst - 1;
+    for (int it = 0; it < n_steps; ++it) {
+        const int ahead = (n_steps - 1 - it < nst - 2) ? n_steps - 1 - it : nst - 2;
+        tc_wait_vmcnt(ahead * lps);
+        __builtin_amdgcn_s_barrier();
+        if (it + nst - 1 < n_steps) issue(wr_slot);
+        const char *sb = lds + rd_slot * stage_bytes;
+        rd_slot = (rd_slot + 1 == nst) ? 0 : rd_slot + 1;
+        wr_slot = (wr_slot + 1 == nst) ? 0 : wr_slot + 1;
+        // straight-line code for each possible number of rank blocks: every LDS read of the stage is
+        // issued before the first MFMA, so their latencies overlap instead of adding up per block
+        switch (nb) {
+        case 1: compute(std::integral_constant<int, 1>{}, sb); break;
+        case 2: compute(std::integral_constant<int, 2>{}, sb); break;
+        case 3: compute(std::integral_constant<int, 3>{}, sb); break;
+        case 4: compute(std::integral_constant<int, 4>{}, sb); break;
+        case 5: compute(std::integral_constant<int, 5>{}, sb); break;
+        case 6: compute(std::integral_constant<int, 6>{}, sb); break;
+        case 7: compute(std::integral_constant<int, 7>{}, sb); break;
+        default: compute(std::integral_constant<int, 8>{}, sb); break;
         }
     }
 
@@ -239,7 +276,7 @@ int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters)
 {
     if (n_active_adapters <= 0) return 1;
     const int64_t wgs = (C + TC_BC - 1) / TC_BC * n_active_adapters;
-    int want = (int)((768 + wgs - 1) / wgs);
+    int want = (int)((1024 + wgs - 1) / wgs);              // two workgroups fit on each of the 256 compute units
     int cap = (int)(h.T / TC_BT / n_active_adapters / 4);     // keep about four stages per split at least
     if (cap < 1) cap = 1;
     if (want > cap) want = cap;
@@ -252,7 +289,14 @@ hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool
                                    int r16_total, hipStream_t st)
 {
     if (h.n_adapters == 0) return hipSuccess;
-    const size_t lds = (size_t)TC_NST * (TC_S_BYTES + (h.max_r16 > 0 ? h.max_r16 : 16) * TC_BT * 2);
+    const size_t stage = TC_S_BYTES + (size_t)(h.max_r16 > 0 ? h.max_r16 : 16) * TC_BT * 2;
+    int nst = (int)(TC_LDS_BYTES / stage);
+    nst = nst > TC_MAX_NST ? TC_MAX_NST : nst;
+    const size_t lds = nst * stage;
+    float *p = n_split > 1 ? part : nullptr;
+    const dim3 grid((unsigned)((C + TC_BC - 1) / TC_BC), (unsigned)h.n_adapters, (unsigned)n_split);
+    const uint16_t *s16 = static_cast<const uint16_t *>(S), *z16 = static_cast<const uint16_t *>(zt);
+    const uint16_t *zero16 = static_cast<const uint16_t *>(zero);
     static size_t allowed[2] = {0, 0};
     if (lds > allowed[want_dA ? 1 : 0]) {
         const void *f = want_dA ? reinterpret_cast<const void *>(k_tokc<true>) : reinterpret_cast<const void *>(k_tokc<false>);
@@ -260,12 +304,8 @@ hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool
         if (e != hipSuccess) return e;
         allowed[want_dA ? 1 : 0] = lds;
     }
-    float *p = n_split > 1 ? part : nullptr;
-    const dim3 grid((unsigned)((C + TC_BC - 1) / TC_BC), (unsigned)h.n_adapters, (unsigned)n_split);
-    const uint16_t *s16 = static_cast<const uint16_t *>(S), *z16 = static_cast<const uint16_t *>(zt);
-    const uint16_t *zero16 = static_cast<const uint16_t *>(zero);
-    if (want_dA) hipLaunchKernelGGL(k_tokc<true>, grid, dim3(256), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total);
-    else hipLaunchKernelGGL(k_tokc<false>, grid, dim3(256), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total);
+    if (want_dA) hipLaunchKernelGGL(k_tokc<true>, grid, dim3(64 * TC_NW), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total, nst);
+    else hipLaunchKernelGGL(k_tokc<false>, grid, dim3(64 * TC_NW), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total, nst);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || n_split <= 1) return e;
     const dim3 g2((unsigned)((C + 255) / 256), (unsigned)r16_total);
