@@ -10,10 +10,13 @@
 // batch; a tile that straddles segments runs the extension of each segment it touches with the
 // rows of the other segments pointed at a page of zeros.
 //
-// Tile: 256 x 256 outputs per workgroup, 64-deep K steps, 8 waves (2 along rows x 4 along
+// Tile: 256 x 256 outputs per workgroup, 64-deep K steps (stages), 8 waves (2 along rows x 4 along
 // columns, 128 x 64 outputs each).  Operands go HBM -> LDS directly (global_load_lds, 16 bytes per
-// lane) into two stages of 64 KB; the 16-byte chunks of a row are XOR-swizzled on the way in (by choosing
-// which chunk each lane fetches) so that MFMA operand reads are free of bank conflicts.
+// lane); the 16-byte chunks of a row are XOR-swizzled on the way in (by choosing which chunk each
+// lane fetches) so that MFMA operand reads are free of bank conflicts.  A stage is fetched as four
+// granules of 16 KB (the two row halves of the S-side tile, two halves of the W-side tile), each
+// kind in its own small ring, 160 KB of LDS in all; the two waves that share a SIMD alternate
+// between multiplying from registers and fetching (LDS -> registers, plus one granule HBM -> LDS).
 // W is [d_in][d_out] row-major in both directions: backward contracts over its contiguous index
 // and reads operands with ds_read_b128; forward contracts over its row index and reads operands
 // with the transposing LDS load (ds_read_b64_tr_b16), so no transposed copy of W is ever made.
@@ -59,27 +62,29 @@ template <int N> __device__ inline void wait_vmcnt()
 }
 
 constexpr int BK = 64;                       // contraction elements per stage
-constexpr int CPR = BK / 8;                  // 16-byte chunks per S-side row
-constexpr int RPI = 64 / CPR;                // S-side rows per 1 KB load instruction
-constexpr int kATile = BM * BK * 2;          // 32 KB
-constexpr int kStage = (BM + BN) * BK * 2;   // 64 KB
-constexpr int kGemmLds = 2 * kStage;         // two stages
 constexpr int KS = BK / 16;                  // MFMA K steps per stage (4)
-static_assert(kRankPadGemm % BK == 0, "extension steps must be whole stages");
-static_assert(KS == 4, "the schedule below is written for four MFMA steps per stage");
-
+constexpr int GR = 16384;                    // bytes of a granule: 128 rows x 64 k, or 32 k x 256 n
+constexpr int kXL = 0, kXT = 2 * GR, kWA = 4 * GR, kWB = 7 * GR;   // rings: 2 + 2 + 3 + 3 granules
+constexpr int kGemmLds = 10 * GR;            // all 160 KB of a compute unit
 constexpr int WN = 2;                        // 32-column blocks per wave: 8 waves of 128 x 64 outputs
-constexpr int AFTER = 2;                     // load pairs of the next-but-one stage issued right behind the barrier;
-                                             // the rest follow behind the first MFMA step of the next stage
+constexpr int NL = 4;                        // load instructions (1 KB each) per wave per granule
+constexpr int kGemmGrid = 256;               // persistent grid: one workgroup per compute unit of an MI355X
+static_assert(kRankPadGemm % BK == 0, "extension steps must be whole stages");
+static_assert(KS == 4 && BM == 256 && BN == 256, "the schedule below is written for this tile");
+
+__device__ inline void wait_vmcnt_048(int n)
+{
+    if (n >= 8) wait_vmcnt<8>();
+    else if (n >= 4) wait_vmcnt<4>();
+    else wait_vmcnt<0>();
+}
+
 template <bool FWD>
 __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__restrict__ S,
                                               const uint16_t *__restrict__ W, const uint16_t *__restrict__ side,
                                               const uint16_t *__restrict__ ap, const uint16_t *__restrict__ zero,
                                               uint16_t *__restrict__ Cout, int tiles_m, int tiles_n)
 {
-    constexpr int NW = 2 * (BN / (WN * 32));     // waves per workgroup
-    constexpr int NL = BM / RPI / NW;            // load instructions per wave per stage, each side
-    static_assert(AFTER <= NL, "");
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int M = (int)mv.hdr->T;
     const int Kd = (int)(FWD ? mv.hdr->D : mv.hdr->K);
@@ -87,89 +92,117 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
     const int ldw = (int)mv.hdr->K;
     const int n_seg = mv.hdr->n_seg;
 
-    // ---- workgroup -> tile.  Workgroups are dealt round-robin to the 8 XCDs (each with its own L2);
-    // give every XCD a contiguous range of tile ids, and walk tile ids in groups of 4 row tiles so
-    // that the tiles resident on one XCD at a time share rows of S and columns of W.
-    int tile = blockIdx.x;
-    {
-        const int nt = tiles_m * tiles_n, per = nt / 8;
+    // ---- workgroup -> tiles.  The grid is persistent (one workgroup per compute unit, each walks the
+    // tile ids b, b + grid, b + 2 grid, ...).  Workgroups are dealt round-robin to the 8 XCDs (each with
+    // its own L2); give every XCD a contiguous range of tile ids, and walk tile ids in groups of 4 row
+    // tiles so that the tiles resident on one XCD at a time share rows of S and columns of W.
+    const int n_tiles = tiles_m * tiles_n;
+    int m0 = 0, n0 = 0, m1 = 0;
+    auto set_tile = [&](int vb) {
+        int tile = vb;
+        const int per = n_tiles / 8;
         if (tile < per * 8) tile = (tile % 8) * per + tile / 8;
-    }
-    constexpr int GM = 4;
-    int tm, tn;
-    {
+        constexpr int GM = 4;
         const int group = tile / (GM * tiles_n), first = group * GM;
         const int gsz = (tiles_m - first < GM) ? tiles_m - first : GM;
         const int in = tile - group * GM * tiles_n;
-        tm = first + in % gsz;
-        tn = in / gsz;
-    }
-    const int m0 = tm * BM, n0 = tn * BN;
-    const int m1 = (m0 + BM < M) ? m0 + BM : M;
+        m0 = (first + in % gsz) * BM;
+        n0 = (in / gsz) * BN;
+        m1 = (m0 + BM < M) ? m0 + BM : M;
+    };
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform: LDS bases stay scalar
+    const int grp = wave >> 2;              // 0: leading group (tile rows 0..127), 1: trailing group (rows 128..255)
+    const int w4 = wave & 3;
 
-    // ---- loader.  S-side tile [256 rows][8 chunks]: instruction q covers rows 8q..8q+7; lane ->
-    // (row 8q + lane/8, slot lane%8); slot c' of row u holds chunk c' ^ ((u >> 1) & 7).
-    // Wave w issues instructions w, w+NW, w+2NW, ...
-    const int a_row = wave * RPI + lane / CPR;                        // + 8*NW*jj
-    const int a_chunk = (lane % CPR) ^ ((a_row >> 1) & 7);            // 8*NW*jj leaves bits 1..3 alone
-    // backward W-side tile [256 n][8 chunks]: same scheme.  forward W-side tile [64 k][32 chunks]:
-    // instruction q covers k rows 2q, 2q+1; lane -> (k row 2q + lane/32, slot lane%32); slot c' of
-    // k row u holds chunk c' ^ (4 * (u & 3)).
-    const int b_row = FWD ? wave * 2 + (lane >> 5) : a_row;          // + 2*NW*jj (FWD) / + 8*NW*jj
+    // ---- loader.  The four waves of a group fetch one granule per read phase, four 1 KB instructions
+    // each (instruction q = w4 + 4 jj).  The leading group fetches the S-side rows of the trailing group
+    // and the second W-side half, the trailing group the S-side rows of the leading group and the first
+    // W-side half (who fetches what only follows from when its ring slot comes free, see the schedule).
+    // S-side granule [128 rows][8 chunks]: instruction q covers rows 8q..8q+7, lane -> (row 8q + lane/8,
+    // slot lane%8), slot c' of row u holds chunk c' ^ ((u >> 1) & 7).  Backward W-side granule
+    // [128 n][8 chunks]: the same.  Forward W-side granule [32 k][32 chunks]: instruction q covers k rows
+    // 2q, 2q+1, lane -> (k row 2q + lane/32, slot lane%32), slot c' of k row u holds chunk c' ^ (4 (u & 3)).
+    const int x_half = grp ^ 1, w_half = grp ^ 1;
+    const int a_row = w4 * 8 + lane / 8;                              // + 32 jj, row inside the granule
+    const int a_chunk = (lane % 8) ^ ((a_row >> 1) & 7);              // 32 jj leaves bits 1..3 alone
+    const int b_row = FWD ? w4 * 2 + (lane >> 5) : a_row;             // + 8 jj (forward: k row) / + 32 jj
     const int b_chunk = FWD ? ((lane & 31) ^ (4 * (b_row & 3))) : a_chunk;
 
-    // running global pointers of the main K loop (rows past the end are clamped: they only feed
-    // outputs that are never stored)
-    const uint16_t *pa[NL], *pb[NL];
+    // Full main K steps are fetched as (uniform base that advances per stage) + (per-lane byte offset
+    // inside the tile that never changes).  Rows and columns past the end are clamped: they only feed
+    // outputs that are never stored.
+    uint32_t off_x[NL], off_w[NL];
+    const char *base_x = nullptr, *base_w = nullptr;
+    const int64_t step_w = FWD ? (int64_t)BK * ldw * 2 : (int64_t)BK * 2;
+    auto set_addresses = [&]() {
 #pragma unroll
-    for (int jj = 0; jj < NL; ++jj) {
-        int row = m0 + a_row + 8 * NW * jj;
-        row = row < M ? row : M - 1;
-        pa[jj] = S + (int64_t)row * Kd + a_chunk * 8;
-        if (FWD) {
-            int n = n0 + b_chunk * 8;
-            n = n < N ? n : N - 8;
-            pb[jj] = W + (int64_t)(b_row + 2 * NW * jj) * ldw + n;
-        } else {
-            int n = n0 + b_row + 8 * NW * jj;
-            n = n < N ? n : N - 1;
-            pb[jj] = W + (int64_t)n * ldw + b_chunk * 8;
+        for (int jj = 0; jj < NL; ++jj) {
+            int row = m0 + x_half * 128 + a_row + 32 * jj;
+            row = row < M ? row : M - 1;
+            off_x[jj] = (uint32_t)(row - m0) * (uint32_t)Kd * 2u + (uint32_t)a_chunk * 16u;
+            if (FWD) {
+                int n = n0 + b_chunk * 8;
+                n = n < N ? n : N - 8;
+                off_w[jj] = (uint32_t)(w_half * 32 + b_row + 8 * jj) * (uint32_t)ldw * 2u + (uint32_t)(n - n0) * 2u;
+            } else {
+                int n = n0 + w_half * 128 + b_row + 32 * jj;
+                n = n < N ? n : N - 1;
+                off_w[jj] = (uint32_t)(n - n0) * (uint32_t)ldw * 2u + (uint32_t)b_chunk * 16u;
+            }
         }
-    }
-    const int64_t pb_step = FWD ? (int64_t)BK * ldw : BK;
+        base_x = reinterpret_cast<const char *>(S) + (int64_t)m0 * Kd * 2;
+        base_w = reinterpret_cast<const char *>(W) + (FWD ? (int64_t)n0 * 2 : (int64_t)n0 * ldw * 2);
+    };
 
+    // Stages of a tile: the main K steps, then one extension step per 64 padded rank columns of every
+    // segment with an adapter that overlaps the rows of the tile.
     const int nk_main = (Kd + BK - 1) / BK;
-    int ext_seg = next_ext_seg(mv, 0, m0, m1), ext_kk = 0;
-    int n_ext = 0;
-    for (int s = ext_seg; s < n_seg; s = next_ext_seg(mv, s + 1, m0, m1))
-        n_ext += mv.seg[s].rp / BK;
-    const int n_it = nk_main + n_ext;
+    int ext_seg = 0, ext_kk = 0, n_it = 0;
+    auto scan_segments = [&]() {
+        ext_seg = next_ext_seg(mv, 0, m0, m1);
+        ext_kk = 0;
+        int n_ext = 0;
+        for (int s = ext_seg; s < n_seg; s = next_ext_seg(mv, s + 1, m0, m1))
+            n_ext += mv.seg[s].rp / BK;
+        n_it = nk_main + n_ext;
+    };
 
-    // Per-lane source addresses of the 4 + 4 loads of stage `it`, in stage order (called once per
-    // stage, with it = 0, 1, 2, ...).  Full main steps just hand out the running pointers; the last,
-    // partial K step masks chunks past the end of the contraction with a page of zeros; the
-    // low-rank extension steps of segment ext_seg read the bf16 low-rank factor of the rows that
-    // belong to that segment (zeros for the other rows of the tile) and B_k or the padded A_k.
-    const uint16_t *na[NL], *nb[NL];
-    auto prepare = [&](int it) {
+    // The direct-to-LDS loads are issued through inline assembly: the compiler, which cannot tell
+    // the granule being filled from the one being read, would otherwise make every LDS read wait
+    // for all of them (vmcnt(0)) and serialise the pipeline.  Ordering is explicit instead: a
+    // counted s_waitcnt plus a bare barrier before a granule is read (__syncthreads would add a
+    // fence that drains every load in flight).  M0 holds the wave-uniform LDS destination; lane i
+    // lands at M0 + 16 i.
+    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
+    auto load_ptr = [&](const void *g, uint32_t dst) {
+        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst));
+    };
+    auto load_off = [&](uint32_t off, const char *base, uint32_t dst) {
+        asm volatile("s_mov_b32 m0, %2\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(off), "s"(base), "s"(dst));
+    };
+    // A wave fetches, stage after stage, first its W-side granule and then its S-side granule.
+    // issue_w(it, slot) / issue_x(it, slot) issue the four loads of that granule of stage `it` into
+    // ring slot `slot`; issue_x also moves the cursor over the low-rank extension steps.  The last,
+    // partial main K step masks chunks past the end of the contraction with a page of zeros; the
+    // extension steps of segment ext_seg read the bf16 low-rank factor of the rows that belong to
+    // that segment (zeros for the other rows of the tile) and B_k or the padded A_k.
+    auto issue_w = [&](int it, int slot) {
+        const uint32_t dst = lds_base + (w_half ? kWB : kWA) + slot * GR + w4 * 1024;
         if (it < nk_main) {
             const int k0 = it * BK;
+            const char *gw = base_w + (int64_t)it * step_w;
             if (k0 + BK <= Kd) {
 #pragma unroll
-                for (int jj = 0; jj < NL; ++jj) { na[jj] = pa[jj]; nb[jj] = pb[jj]; }
+                for (int jj = 0; jj < NL; ++jj) load_off(off_w[jj], gw, dst + jj * 4096);
             } else {
 #pragma unroll
                 for (int jj = 0; jj < NL; ++jj) {
-                    na[jj] = (k0 + a_chunk * 8 < Kd) ? pa[jj] : zero;
-                    const bool ok = FWD ? (k0 + b_row + 2 * NW * jj < Kd) : (k0 + b_chunk * 8 < Kd);
-                    nb[jj] = ok ? pb[jj] : zero;
+                    const bool ok = FWD ? (k0 + w_half * 32 + b_row + 8 * jj < Kd) : (k0 + b_chunk * 8 < Kd);
+                    load_ptr(ok ? static_cast<const void *>(gw + off_w[jj]) : zero, dst + jj * 4096);
                 }
             }
-#pragma unroll
-            for (int jj = 0; jj < NL; ++jj) { pa[jj] += BK; pb[jj] += pb_step; }
         } else {
             const int sidx = __builtin_amdgcn_readfirstlane(ext_seg);
             const int kk = __builtin_amdgcn_readfirstlane(ext_kk);
@@ -177,49 +210,59 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
             const AdapterInfo a = mv.ad[g.adapter];
 #pragma unroll
             for (int jj = 0; jj < NL; ++jj) {
-                const int row = m0 + a_row + 8 * NW * jj;
-                const bool in = row >= g.row0 && row < g.row1;
-                na[jj] = in ? side + g.hb_off + (int64_t)(row - g.row0) * g.rp + kk + a_chunk * 8 : zero;
+                const uint16_t *gw;
                 if (FWD) {
-                    const int j = kk + b_row + 2 * NW * jj;            // row of B_k
+                    const int j = kk + w_half * 32 + b_row + 8 * jj;   // row of B_k
                     int n = n0 + b_chunk * 8;
                     n = n < N ? n : N - 8;
-                    nb[jj] = (j < g.r) ? static_cast<const uint16_t *>(a.B) + (int64_t)j * ldw + n : zero;
+                    gw = (j < g.r) ? static_cast<const uint16_t *>(a.B) + (int64_t)j * ldw + n : zero;
                 } else {
-                    int n = n0 + b_row + 8 * NW * jj;                  // row of padded A_k
+                    int n = n0 + w_half * 128 + b_row + 32 * jj;       // row of padded A_k
                     n = n < N ? n : N - 1;
-                    nb[jj] = ap + a.ap_off + (int64_t)n * g.rp + kk + b_chunk * 8;
+                    gw = ap + a.ap_off + (int64_t)n * g.rp + kk + b_chunk * 8;
                 }
+                load_ptr(gw, dst + jj * 4096);
+            }
+        }
+    };
+    auto issue_x = [&](int it, int slot) {
+        const uint32_t dst = lds_base + (x_half ? kXT : kXL) + slot * GR + w4 * 1024;
+        if (it < nk_main) {
+            const int k0 = it * BK;
+            const char *gx = base_x + (int64_t)k0 * 2;
+            if (k0 + BK <= Kd) {
+#pragma unroll
+                for (int jj = 0; jj < NL; ++jj) load_off(off_x[jj], gx, dst + jj * 4096);
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < NL; ++jj) {
+                    const bool ok = k0 + a_chunk * 8 < Kd;
+                    load_ptr(ok ? static_cast<const void *>(gx + off_x[jj]) : zero, dst + jj * 4096);
+                }
+            }
+        } else {
+            const int sidx = __builtin_amdgcn_readfirstlane(ext_seg);
+            const int kk = __builtin_amdgcn_readfirstlane(ext_kk);
+            const SegInfo g = mv.seg[sidx];
+#pragma unroll
+            for (int jj = 0; jj < NL; ++jj) {
+                const int row = m0 + x_half * 128 + a_row + 32 * jj;
+                const bool in = row >= g.row0 && row < g.row1;
+                load_ptr(in ? side + g.hb_off + (int64_t)(row - g.row0) * g.rp + kk + a_chunk * 8 : zero, dst + jj * 4096);
             }
             ext_kk = kk + BK;
             if (ext_kk >= g.rp) { ext_seg = next_ext_seg(mv, sidx + 1, m0, m1); ext_kk = 0; }
         }
     };
-    // The direct-to-LDS loads are issued through inline assembly: the compiler, which cannot tell
-    // the stage being filled from the stage being read, would otherwise make every LDS read wait
-    // for all of them (vmcnt(0)) and serialise the pipeline.  Ordering is explicit instead: a
-    // counted s_waitcnt plus a bare barrier before a stage is read (__syncthreads would add a
-    // fence that drains every load in flight).  M0 holds the wave-uniform LDS destination; lane i
-    // lands at M0 + 16 i.
-    const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
-    auto load_lds16 = [&](const uint16_t *g, uint32_t dst) {
-        asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst));
-    };
-    auto load_pair = [&](int buf, int jj) {
-        const uint32_t sa = lds_base + buf * kStage + (wave + NW * jj) * 1024;
-        load_lds16(na[jj], sa);
-        load_lds16(nb[jj], sa + kATile);
-    };
 
-    // ---- MFMA operand addressing.  Wave (wm, wn) owns rows wm*128.. and columns wn*32*WN..
-    constexpr int WAVES_N = BN / (WN * 32);
-    const int wm0 = (wave / WAVES_N) * 128, wn0 = (wave % WAVES_N) * (WN * 32);
+    // ---- MFMA operand addressing.  Wave (grp, w4) owns rows grp*128.. and columns w4*64..
+    const int wm0 = grp * 128, wn0 = w4 * (WN * 32);
     const int l32 = lane & 31, kg = lane >> 5;
-    // S-side operand (4 blocks of 32 rows): row u = wm0 + mi*32 + l32, chunk = ks*2 + kg
+    // S-side operand (4 blocks of 32 rows of the wave's own granule): row u = mi*32 + l32, chunk = ks*2 + kg
     int xoff[4];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
-        const int u = wm0 + mi * 32 + l32;
+        const int u = mi * 32 + l32;
         xoff[mi] = u * (BK * 2) + ((kg ^ ((u >> 1) & 7)) * 16);          // ks*2 XORs in separately (bit 1 and up)
     }
     // W-side operand (WN blocks of 32 columns)
@@ -230,133 +273,198 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
         if (FWD) {
             // transposing read: the 16 lanes of a group fetch a 4(k) x 16(n) block, 8 bytes each
             const int nl = wn0 + ni * 32 + (g4 & 1) * 16 + (i16 & 3) * 4;   // first column this lane fetches
-            const int kr = (g4 >> 1) * 8 + (i16 >> 2);                      // + ks*16, + 4 for the second read
+            const int kr = (g4 >> 1) * 8 + (i16 >> 2);                      // + 16 for the second K step, + 4 for the second read
             woff[ni] = kr * 512 + ((((nl >> 3) ^ (4 * (kr & 3))) * 16) + (nl & 7) * 2);
         } else {
-            const int u = wn0 + ni * 32 + l32;
+            const int u = (wn0 & 127) + ni * 32 + l32;                      // row inside the wave's W-side half
             woff[ni] = u * (BK * 2) + ((kg ^ ((u >> 1) & 7)) * 16);
         }
     }
 
     f32x16 acc[WN][4];
+
+    // MFMA operands of half a stage (two K steps of 16): 8 S-side + 4 W-side fragments.
+    // xs: slot of the wave's S-side granule; wa, wb: slots of the two W-side halves (byte offsets in LDS).
+    bf16x8 xf[2][4], wf[2][WN];
+    auto read_half = [&](int xs, int wa, int wb, int h) {
+        const char *sx = lds + xs;
+        // forward: K half h of the stage is W-side half h; backward: the wave's columns lie in one half
+        const char *sw = lds + (FWD ? (h ? wb : wa) : (wn0 >= 128 ? wb : wa));
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2) {
+            const int ks = 2 * h + k2;
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+                xf[k2][mi] = *LDS_PTR(const bf16x8, sx + (xoff[mi] ^ (ks * 32)));
+#pragma unroll
+            for (int ni = 0; ni < WN; ++ni) {
+                if (FWD) {
+                    const char *p = sw + woff[ni] + k2 * 16 * 512;
+                    bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p));
+                    bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p + 4 * 512));
+                    wf[k2][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                } else {
+                    wf[k2][ni] = *LDS_PTR(const bf16x8, sw + (woff[ni] ^ (ks * 32)));
+                }
+            }
+        }
+    };
+    auto mfma_half = [&]() {
+#pragma unroll
+        for (int k2 = 0; k2 < 2; ++k2)
+#pragma unroll
+            for (int ni = 0; ni < WN; ++ni)
+#pragma unroll
+                for (int mi = 0; mi < 4; ++mi)
+                    acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[k2][ni], xf[k2][mi], acc[ni][mi], 0, 0, 0);
+    };
+    // workgroup barrier that the compiler may move nothing across: neither memory accesses nor MFMAs
+    // (the phases below only work if each instruction stays in the phase it was written in)
+    auto barrier = [&]() {
+        asm volatile("" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");
+    };
+
+    // ---- schedule.  Time runs in phases of half a stage, one barrier each.  The two waves that share a
+    // SIMD (w and w + 4) alternate roles: while one issues the 16 MFMAs of a half stage back to back
+    // from registers, the other reads the operands of its next half stage from LDS and issues one
+    // granule of direct loads.  The leading group reads half h of stage s in phase 4s + 2h and multiplies
+    // in the next phase; the trailing group runs one phase behind.  Last reads of the granules of stage s:
+    //   S rows of the leading group: phase 4s+2      S rows of the trailing group: phase 4s+3
+    //   W halves: phase 4s+3
+    // With rings of 2, 2, 3 and 3 slots the granules of stage s can be fetched in the phases
+    //   first W half 4s-7 (trailing group), second W half 4s-6 (leading), leading S rows 4s-5 (trailing),
+    //   trailing S rows 4s-4 (leading),
+    // one granule per phase, each four phases or more before the phase that ends with the wait for it.
+    // A wave waits, at the end of each of its read phases, until all but the last two granules it has
+    // issued are complete; the barrier that follows publishes them.
+    int gi = 0;                               // granules this wave has issued (stage s: W granule 2s, S granule 2s+1)
+    auto wait_done = [&](int need) {          // granules 0..need of this wave complete (no-op past the last one)
+        int after = gi - 1 - (need < 2 * n_it ? need : 2 * n_it - 1);
+        wait_vmcnt_048(4 * (after < 0 ? 0 : after));
+    };
+    // Prologue of a tile: both groups fetch their granules of stages 0 and 1 (the leading group leaves the
+    // S granule of stage 1 to its first read phase).  With two main K steps or more these loads do not
+    // depend on the segment table, which is then scanned while they are in flight.
+    auto prologue = [&]() {
+        set_addresses();
+        if (nk_main < 2) scan_segments();
+        issue_w(0, 0); issue_x(0, 0); gi = 2;
+        if (nk_main >= 2 || n_it > 1) {
+            issue_w(1, 1); ++gi;
+            if (grp == 1) { issue_x(1, 1); ++gi; }
+        }
+        if (nk_main >= 2) scan_segments();
+    };
+
+    int vb = blockIdx.x;
+    set_tile(vb);
+    prologue();
+    while (true) {
 #pragma unroll
     for (int ni = 0; ni < WN; ++ni)
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[ni][mi][i] = 0.f;
+    wait_done(grp == 1 ? 1 : 0);              // leading group: its S granule of stage 0 is only read in phase 1
+    barrier();
 
-    // MFMA operands of one K step (16 deep): 4 S-side + 2 W-side fragments, double-buffered in registers
-    bf16x8 xf[2][4], wf[2][WN];
-    auto read_frags = [&](int buf, int ks, int f) {
-        const char *sa = lds + buf * kStage;
-        const char *sb = sa + kATile;
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi)
-            xf[f][mi] = *LDS_PTR(const bf16x8, sa + (xoff[mi] ^ (ks * 32)));
-#pragma unroll
-        for (int ni = 0; ni < WN; ++ni) {
-            if (FWD) {
-                // k rows advance by 16 per ks (16*512 bytes): bits above the swizzle, plain add
-                const char *p = sb + woff[ni] + ks * 16 * 512;
-                bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p));
-                bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16(LDS_PTR(bf16x4, p + 4 * 512));
-                wf[f][ni] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            } else {
-                wf[f][ni] = *LDS_PTR(const bf16x8, sb + (woff[ni] ^ (ks * 32)));
-            }
+    if (grp == 0) {
+        // leading group
+        int s3 = 0;                           // s % 3
+        for (int s = 0; s < n_it; ++s) {
+            const int xs = kXL + (s & 1) * GR, wa = kWA + s3 * GR, wb = kWB + s3 * GR;
+            const int s3n = s3 == 2 ? 0 : s3 + 1, s3nn = s3n == 2 ? 0 : s3n + 1;
+            // phase 4s: read half 0; fetch the trailing group's S rows of stage s+1
+            read_half(xs, wa, wb, 0);
+            if (s + 1 < n_it) { issue_x(s + 1, (s + 1) & 1); ++gi; }
+            __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): operands in registers before the roles swap
+            wait_done(2 * s + 1);
+            barrier();
+            mfma_half();                      // phase 4s+1
+            barrier();
+            // phase 4s+2: read half 1; fetch the second W half of stage s+2
+            read_half(xs, wa, wb, 1);
+            if (s + 2 < n_it) { issue_w(s + 2, s3nn); ++gi; }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            wait_done(2 * s + 2);
+            barrier();
+            mfma_half();                      // phase 4s+3
+            barrier();
+            s3 = s3n;
         }
-    };
-    auto mfma_step = [&](int f) {
-#pragma unroll
-        for (int ni = 0; ni < WN; ++ni)
-#pragma unroll
-            for (int mi = 0; mi < 4; ++mi)
-                acc[ni][mi] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[f][ni], xf[f][mi], acc[ni][mi], 0, 0, 0);
-    };
-    // issue order of a step: the LDS reads of the next step go out one by one behind the first MFMAs
-    auto interleave_reads = [&]() {
-        constexpr int n_ds = 4 + (FWD ? 2 * WN : WN), n_mfma = 4 * WN;
-#pragma unroll
-        for (int i = 0; i < n_ds; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // 1 MFMA
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   // 1 LDS read
-        }
-        if (n_ds < n_mfma) __builtin_amdgcn_sched_group_barrier(0x008, n_mfma - n_ds, 0);
-    };
-
-    // ---- schedule.  Stage p lives in buffer p % 2.  The loads of stage p+2 are issued right after the
-    // barrier that ends the reading of stage p (same buffer), so they have a whole stage of MFMA work
-    // to land.  That barrier sits before the last MFMA step of stage p: the operands of that step are
-    // already in registers, so the first LDS reads of stage p+1 are hidden behind its MFMAs.
-    prepare(0);
-#pragma unroll
-    for (int jj = 0; jj < NL; ++jj) load_pair(0, jj);
-    if (n_it > 1) {
-        prepare(1);
-#pragma unroll
-        for (int jj = 0; jj < NL; ++jj) load_pair(1, jj);
-        wait_vmcnt<2 * NL>();                 // stage 0 landed (the 2 NL loads of stage 1 may still be in flight)
+        barrier();                            // phase 4 n_it: the trailing group multiplies its last half
     } else {
-        wait_vmcnt<0>();
+        // trailing group
+        barrier();                            // phase 0
+        int s3 = 0;
+        for (int s = 0; s < n_it; ++s) {
+            const int xs = kXT + (s & 1) * GR, wa = kWA + s3 * GR, wb = kWB + s3 * GR;
+            const int s3n = s3 == 2 ? 0 : s3 + 1, s3nn = s3n == 2 ? 0 : s3n + 1;
+            // phase 4s+1: read half 0; fetch the first W half of stage s+2
+            read_half(xs, wa, wb, 0);
+            if (s + 2 < n_it) { issue_w(s + 2, s3nn); ++gi; }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            wait_done(2 * s + 2);
+            barrier();
+            mfma_half();                      // phase 4s+2
+            barrier();
+            // phase 4s+3: read half 1; fetch the leading group's S rows of stage s+2
+            read_half(xs, wa, wb, 1);
+            if (s + 2 < n_it) { issue_x(s + 2, s & 1); ++gi; }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            wait_done(2 * s + 3);
+            barrier();
+            mfma_half();                      // phase 4s+4
+            barrier();
+            s3 = s3n;
+        }
     }
-    if (n_it > 2) prepare(2);               // pointers of stage p+2 are ready before the barrier of stage p
-    __builtin_amdgcn_s_barrier();
-    read_frags(0, 0, 0);
+    // Every LDS read of this tile has been issued and waited for: the rings are free.  Start fetching the
+    // next tile before storing this one, so that its first loads fly during the stores.
+    const int em0 = m0, en0 = n0;
+    vb += gridDim.x;
+    const bool more = vb < n_tiles;
+    if (more) {
+        set_tile(vb);
+        prologue();
+    }
 
-    bool pending = false;                     // load pairs AFTER..NL-1 of the stage being fetched still to issue
-    for (int p = 0; p + 1 < n_it; ++p) {
-        const int buf = p & 1;
-        read_frags(buf, 1, 1); mfma_step(0); interleave_reads();
-        if (AFTER < NL && pending) {
-#pragma unroll
-            for (int jj = AFTER; jj < NL; ++jj) load_pair(buf ^ 1, jj);
-        }
-        read_frags(buf, 2, 0); mfma_step(1); interleave_reads();
-        read_frags(buf, 3, 1); mfma_step(0); interleave_reads();
-        if (p + 2 < n_it && p > 0) prepare(p + 2);
-        // every read of stage p has been issued; make sure this wave's have completed, then wait for
-        // stage p+1 (its loads were issued about one stage ago) and for everybody else
-        wait_vmcnt<0>();
-        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0), other counters untouched
-        __builtin_amdgcn_s_barrier();
-        read_frags(buf ^ 1, 0, 0);
-        pending = p + 2 < n_it;
-        if (pending) {                        // refill the buffer that has just been released
-#pragma unroll
-            for (int jj = 0; jj < AFTER; ++jj) load_pair(buf, jj);
-        }
-        mfma_step(1);
-    }
+    // ---- epilogue: MFMA rows are output columns n, MFMA columns are output rows m: a lane holds, for
+    // each group i4 of 4 registers, 4 consecutive n of one m.  Stored straight from there, every store
+    // instruction would touch 32 rows with 16 bytes each; instead each wave passes its 32 x 64 blocks
+    // through 4 KB of LDS of its own (the third slots of the W rings, which the prologue of the next
+    // tile does not touch) and stores whole 128-byte rows, 16 bytes per lane.
     {
-        const int buf = (n_it - 1) & 1;
-        read_frags(buf, 1, 1); mfma_step(0); interleave_reads();
-        read_frags(buf, 2, 0); mfma_step(1); interleave_reads();
-        read_frags(buf, 3, 1); mfma_step(0); interleave_reads();
-        mfma_step(1);
-    }
-    wait_vmcnt<0>();                          // no direct-to-LDS load may outlive the workgroup
-
-    // ---- epilogue: MFMA rows are output columns n, MFMA columns are output rows m.
-    // Lane holds, for each group i4 of 4 registers, 4 consecutive n of one m: one 8-byte store.
+        char *stg = lds + (grp == 0 ? kWA : kWB) + 2 * GR + w4 * 4096;
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
-        const int m = m0 + wm0 + mi * 32 + l32;
-        if (m >= M) continue;
-        uint16_t *crow = Cout + (int64_t)m * N;
+        for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
-        for (int ni = 0; ni < WN; ++ni)
+            for (int ni = 0; ni < WN; ++ni)
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const int n = n0 + wn0 + ni * 32 + i4 * 8 + kg * 4;
-                if (n < N) {
+                for (int i4 = 0; i4 < 4; ++i4) {
                     uint2 v;
                     v.x = pack_bf16x2(acc[ni][mi][i4 * 4 + 0], acc[ni][mi][i4 * 4 + 1]);
                     v.y = pack_bf16x2(acc[ni][mi][i4 * 4 + 2], acc[ni][mi][i4 * 4 + 3]);
-                    *reinterpret_cast<uint2 *>(crow + n) = v;
+                    const int chunk = ni * 4 + i4;                     // 16-byte chunk of the 128-byte row
+                    *reinterpret_cast<uint2 *>(stg + l32 * 128 + ((chunk ^ (l32 & 7)) * 16) + kg * 8) = v;
                 }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int row = (lane >> 3) + 8 * j, c = lane & 7;
+                const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((c ^ (row & 7)) * 16));
+                const int m = em0 + wm0 + mi * 32 + row, n = en0 + wn0 + c * 8;
+                if (m < M && n < N) *reinterpret_cast<uint4 *>(Cout + (int64_t)m * N + n) = v;
             }
+        }
     }
+    if (!more) break;
+    }
+    wait_vmcnt<0>();                          // no direct-to-LDS load may outlive the workgroup
 }
 
 template <bool FWD>
@@ -373,7 +481,8 @@ static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, const 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
-    hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(512), kGemmLds, st, mv,
+    const int n_tiles = tiles_m * tiles_n;
+    hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < kGemmGrid ? n_tiles : kGemmGrid)), dim3(512), kGemmLds, st, mv,
                        static_cast<const uint16_t *>(S), static_cast<const uint16_t *>(W),
                        static_cast<const uint16_t *>(side), static_cast<const uint16_t *>(ap),
                        static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n);
