@@ -182,9 +182,9 @@ static plora_status prepare(const plora_desc *d, const void *x, const void *W, c
     return PLORA_OK;
 }
 
-static hipError_t upload_meta(const HostMeta &m, char *ws, hipStream_t st, MetaView &mv)
+static void build_blob(const HostMeta &m, char *ws, std::vector<char> &blob, MetaView &mv)
 {
-    std::vector<char> blob(m.ws.meta_bytes);
+    blob.resize(m.ws.meta_bytes);
     char *p = blob.data();
     std::memcpy(p, &m.hdr, sizeof(MetaHeader)); p += sizeof(MetaHeader);
     if (!m.seg.empty()) std::memcpy(p, m.seg.data(), m.seg.size() * sizeof(SegInfo));
@@ -194,9 +194,37 @@ static hipError_t upload_meta(const HostMeta &m, char *ws, hipStream_t st, MetaV
     mv.hdr = reinterpret_cast<const MetaHeader *>(dev);
     mv.seg = reinterpret_cast<const SegInfo *>(dev + sizeof(MetaHeader));
     mv.ad = reinterpret_cast<const AdapterInfo *>(dev + sizeof(MetaHeader) + m.seg.size() * sizeof(SegInfo));
+}
+
+// The small jobs in front of the heavy kernels: metadata blob and zero page into the workspace,
+// packing of A_k (bf16 path), transposed bf16 copy of a saved activation (bf16 backward).  One
+// launch when the blob fits a kernel argument, separate launches otherwise.
+static hipError_t prepare_device(const HostMeta &m, char *ws, hipStream_t st, MetaView &mv, void *at, void *ap,
+                                 bool want_at, bool want_ap, const float *hf, void *zt)
+{
+    std::vector<char> blob;
+    build_blob(m, ws, blob, mv);
+    const bool pack = m.hdr.n_adapters > 0 && (want_at || want_ap);
+    const bool tr = hf && zt && m.hdr.n_blocks > 0;
+    if (prep_fits(blob.size())) {
+        Bracket b(6, st);
+        return launch_prep(m.hdr, ws + m.ws.meta, blob.data(), blob.size(), ws + m.ws.zero, at, ap, pack && want_at,
+                           pack && want_ap, tr ? hf : nullptr, tr ? zt : nullptr, st);
+    }
     hipError_t e = clear_zero_page(ws + m.ws.zero, st);
     if (e != hipSuccess) return e;
-    return upload_blob(dev, blob.data(), blob.size(), st);
+    e = upload_blob(ws + m.ws.meta, blob.data(), blob.size(), st);
+    if (e != hipSuccess) return e;
+    if (pack) {
+        Bracket b(6, st);
+        e = launch_pack_bf16(mv, m.hdr, at, ap, want_at, want_ap, st);
+        if (e != hipSuccess) return e;
+    }
+    if (tr) {
+        Bracket b(7, st);
+        e = launch_h_to_zt(mv, m.hdr, hf, zt, st);
+    }
+    return e;
 }
 
 }  // namespace plora
@@ -297,9 +325,10 @@ plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void 
     char *ws = static_cast<char *>(workspace);
 
     MetaView mv;
-    PL_TRY(upload_meta(m, ws, st, mv));
-    float *hf = h_saved ? h_saved : reinterpret_cast<float *>(ws + m.ws.hf);
     const bool lora = m.hdr.n_blocks > 0;
+    const bool bf = desc->dtype == PLORA_BF16;
+    PL_TRY(prepare_device(m, ws, st, mv, ws + m.ws.at, nullptr, bf && lora, false, nullptr, nullptr));
+    float *hf = h_saved ? h_saved : reinterpret_cast<float *>(ws + m.ws.hf);
 
     if (desc->dtype == PLORA_F32) {
         const float *xf = static_cast<const float *>(x);
@@ -312,9 +341,8 @@ plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void 
     void *at = ws + m.ws.at, *hb = ws + m.ws.hb;
     float *part = reinterpret_cast<float *>(ws + m.ws.part);
     if (lora) {
-        { Bracket b(6, st); PL_TRY(launch_pack_bf16(mv, m.hdr, at, nullptr, true, false, st)); }
-        { Bracket b(2, st);
-          PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, h_saved, hb, nullptr, false, st)); }
+        Bracket b(2, st);
+        PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, h_saved, hb, nullptr, false, st));
     }
     { Bracket b(0, st);
       PL_TRY(launch_gemm_bf16(mv, m.hdr, true, x, W, hb, nullptr, ws + m.ws.zero, y, st)); }
@@ -347,7 +375,12 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
     if (desc->T == 0 && !any_w) return PLORA_OK;
 
     MetaView mv;
-    PL_TRY(upload_meta(m, ws, st, mv));
+    {
+        const bool bf = desc->dtype == PLORA_BF16;
+        const bool need_shrink = any_w && !h_saved;
+        PL_TRY(prepare_device(m, ws, st, mv, ws + m.ws.at, ws + m.ws.ap, bf && lora && need_shrink,
+                              bf && lora && dx != nullptr, (bf && lora && any_w) ? h_saved : nullptr, ws + m.ws.zt_h));
+    }
 
     if (desc->dtype == PLORA_F32) {
         const float *xf = static_cast<const float *>(x), *dyf = static_cast<const float *>(dy);
@@ -376,19 +409,16 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
     float *part = reinterpret_cast<float *>(ws + m.ws.part);
     float *wpart = reinterpret_cast<float *>(ws + m.ws.wpart);
     if (lora) {
-        const bool need_shrink = any_w && !h_saved;
-        { Bracket b(6, st); PL_TRY(launch_pack_bf16(mv, m.hdr, at, ap, need_shrink, dx != nullptr, st)); }
-        if (any_w) {
-            Bracket b(h_saved ? 7 : 2, st);
-            if (h_saved) PL_TRY(launch_h_to_zt(mv, m.hdr, h_saved, zt_h, st));
-            else PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, nullptr, nullptr, zt_h, false, st));
+        if (any_w && !h_saved) {
+            Bracket b(2, st);
+            PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, nullptr, nullptr, zt_h, false, st));
         }
         { Bracket b(3, st);
           PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, ws + m.ws.zero, part, nullptr, gb, any_w ? zt_g : nullptr, true, st)); }
     }
     if (any_w) {
-        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + m.ws.zero, wpart, m.split_dB, m.r16_total, st)); }
-        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + m.ws.zero, wpart, m.split_dA, m.r16_total, st)); }
+        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + m.ws.zero, wpart, m.split_dB, m.r16_total, m.n_active, st)); }
+        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + m.ws.zero, wpart, m.split_dA, m.r16_total, m.n_active, st)); }
     }
     if (dx && desc->T > 0) {
         Bracket b(1, st);

@@ -72,6 +72,11 @@ struct KernelTimer;   // bench-only event bracketing, see plora_api.hip
 
 hipError_t upload_blob(void *dst_dev, const void *src_host, size_t bytes, hipStream_t st);
 hipError_t clear_zero_page(void *zero_dev, hipStream_t st);
+// One launch for blob + zero page + packing of A_k + transposed copy of a saved activation (each optional);
+// only when prep_fits(blob_bytes).
+bool prep_fits(size_t blob_bytes);
+hipError_t launch_prep(const MetaHeader &h, void *meta_dev, const void *blob_host, size_t blob_bytes, void *zero_dev,
+                       void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt, hipStream_t st);
 
 // bf16 path -------------------------------------------------------------------------------------
 // Packs A_k^T (zero rows beyond r) and/or A_k padded to rp columns.
@@ -97,7 +102,7 @@ hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool forwar
 //   n_split > 1: the token walk is split, partial tiles go through `part` ([split][r16_total][C] fp32).
 hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool want_dA, const void *S,
                                    int64_t C, const void *zt, const void *zero, float *part, int n_split,
-                                   int r16_total, hipStream_t st);
+                                   int r16_total, int n_active_adapters, hipStream_t st);
 int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters);
 int skinny_splits(const MetaHeader &h, int64_t C);
 

@@ -53,13 +53,10 @@ hipError_t clear_zero_page(void *zero_dev, hipStream_t st)
 // ap: A_k as [D][rp] with columns j >= r zero - the low-rank K-extension operand of the dX GEMM.
 // One block handles 64 rows i of one adapter; the tile goes through LDS so that both the reads of
 // A_k (contiguous in j) and the writes of A_k^T (contiguous in i) are coalesced.
-__global__ void __launch_bounds__(256) k_pack_a(MetaView mv, uint16_t *at, uint16_t *ap, int want_at, int want_ap)
+__device__ inline void pack_block(const AdapterInfo &a, int64_t D, int bx, uint16_t *at, uint16_t *ap, int want_at,
+                                  int want_ap, uint16_t (*tile)[PLORA_MAX_RANK + 2])
 {
-    __shared__ uint16_t tile[64][PLORA_MAX_RANK + 2];
-    const int k = blockIdx.y;
-    const AdapterInfo a = mv.ad[k];
-    const int64_t D = mv.hdr->D;
-    const int64_t i0 = (int64_t)blockIdx.x * 64;
+    const int64_t i0 = (int64_t)bx * 64;
     const uint16_t *A = static_cast<const uint16_t *>(a.A);
     const int r = a.r;
     const int rows = (int)((D - i0 < 64) ? D - i0 : 64);
@@ -84,6 +81,13 @@ __global__ void __launch_bounds__(256) k_pack_a(MetaView mv, uint16_t *at, uint1
     }
 }
 
+__global__ void __launch_bounds__(256) k_pack_a(MetaView mv, uint16_t *at, uint16_t *ap, int want_at, int want_ap)
+{
+    __shared__ uint16_t tile[64][PLORA_MAX_RANK + 2];
+    const AdapterInfo a = mv.ad[blockIdx.y];
+    pack_block(a, mv.hdr->D, blockIdx.x, at, ap, want_at, want_ap, tile);
+}
+
 hipError_t launch_pack_bf16(const MetaView &mv, const MetaHeader &h, void *at, void *ap, bool want_at,
                             bool want_ap, hipStream_t st)
 {
@@ -104,19 +108,11 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
 
 // zt[j][t] = bf16(h[t][j]); rows j >= r and the padding tokens are written as zero.  Grid: (token
 // block of kSkinnyRows rows, slice of 16 rows inside it).
-__global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, uint16_t *zt)
+__device__ inline void h_to_zt_slice(const SegInfo &g, int blk, int slice, const float *hf, uint16_t *zt,
+                                     float (*tile)[PLORA_MAX_RANK + 1])
 {
     constexpr int FR = 16;
-    __shared__ float tile[FR][PLORA_MAX_RANK + 1];
-    const int blk = blockIdx.x;
-    const int n_seg = mv.hdr->n_seg;
-    int s = 0;
-    for (int q = 0; q < n_seg; ++q) {
-        const SegInfo g = mv.seg[q];
-        if (g.adapter >= 0 && g.row1 > g.row0 && blk >= g.blk0) s = q;
-    }
-    const SegInfo g = mv.seg[s];
-    const int t0 = (blk - g.blk0) * kSkinnyRows + blockIdx.y * FR;   // first token of the slice inside the segment
+    const int t0 = (blk - g.blk0) * kSkinnyRows + slice * FR;   // first token of the slice inside the segment
     if (t0 >= g.lp) return;
     int nt = g.row1 - g.row0 - t0;
     nt = nt < 0 ? 0 : (nt < FR ? nt : FR);
@@ -130,10 +126,92 @@ __global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, u
     }
 }
 
+__global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, uint16_t *zt)
+{
+    __shared__ float tile[16][PLORA_MAX_RANK + 1];
+    const int blk = blockIdx.x;
+    const int n_seg = mv.hdr->n_seg;
+    int s = 0;
+    for (int q = 0; q < n_seg; ++q) {
+        const SegInfo g = mv.seg[q];
+        if (g.adapter >= 0 && g.row1 > g.row0 && blk >= g.blk0) s = q;
+    }
+    const SegInfo g = mv.seg[s];
+    h_to_zt_slice(g, blk, blockIdx.y, hf, zt, tile);
+}
+
 hipError_t launch_h_to_zt(const MetaView &mv, const MetaHeader &h, const float *hf, void *zt, hipStream_t st)
 {
     if (h.n_blocks == 0) return hipSuccess;
     hipLaunchKernelGGL(k_h_to_zt, dim3((unsigned)h.n_blocks, kSkinnyRows / 16), dim3(256), 0, st, mv, hf, static_cast<uint16_t *>(zt));
+    return hipGetLastError();
+}
+
+// ---- fused preparation ---------------------------------------------------------------------------
+// When the whole metadata blob fits one kernel-argument chunk, a single launch does all the small
+// jobs that precede the heavy kernels: block 0 writes the blob and the zero page, the next blocks
+// pack the adapter matrices, the last ones make the transposed bf16 copy of a saved activation.
+// The packing and copy blocks read the metadata from the kernel argument itself, so they do not wait
+// for block 0.
+template <typename T> __device__ inline T read_arg(const BlobChunk &c, int byte_off)
+{
+    static_assert(sizeof(T) % 4 == 0, "metadata structs are made of 32-bit words");
+    union { T v; uint32_t w[sizeof(T) / 4]; } u;
+#pragma unroll
+    for (int i = 0; i < (int)(sizeof(T) / 4); ++i) u.w[i] = c.w[byte_off / 4 + i];
+    return u.v;
+}
+
+__global__ void __launch_bounds__(256) k_prep(BlobChunk c, uint32_t *meta_dst, int n_words, uint32_t *zero_page,
+                                             uint16_t *at, uint16_t *ap, int want_at, int want_ap, int pack_bx,
+                                             int n_pack, const float *hf, uint16_t *zt)
+{
+    __shared__ union {
+        uint16_t pack[64][PLORA_MAX_RANK + 2];
+        float tr[16][PLORA_MAX_RANK + 1];
+    } sh;
+    int b = blockIdx.x;
+    if (b == 0) {
+        for (int i = threadIdx.x; i < n_words; i += 256) meta_dst[i] = c.w[i];
+        zero_page[threadIdx.x] = 0u;     // kZeroBytes = 256 * 4
+        return;
+    }
+    b -= 1;
+    const MetaHeader hdr = read_arg<MetaHeader>(c, 0);
+    const int seg_base = (int)sizeof(MetaHeader);
+    const int ad_base = seg_base + hdr.n_seg * (int)sizeof(SegInfo);
+    if (b < n_pack) {
+        const AdapterInfo a = read_arg<AdapterInfo>(c, ad_base + (b / pack_bx) * (int)sizeof(AdapterInfo));
+        pack_block(a, hdr.D, b % pack_bx, at, ap, want_at, want_ap, sh.pack);
+        return;
+    }
+    b -= n_pack;
+    const int blk = b / (kSkinnyRows / 16), slice = b % (kSkinnyRows / 16);
+    int s = 0;
+    for (int q = 0; q < hdr.n_seg; ++q) {
+        const SegInfo g = read_arg<SegInfo>(c, seg_base + q * (int)sizeof(SegInfo));
+        if (g.adapter >= 0 && g.row1 > g.row0 && blk >= g.blk0) s = q;
+    }
+    const SegInfo g = read_arg<SegInfo>(c, seg_base + s * (int)sizeof(SegInfo));
+    h_to_zt_slice(g, blk, slice, hf, zt, sh.tr);
+}
+
+bool prep_fits(size_t blob_bytes) { return blob_bytes <= sizeof(BlobChunk); }
+
+hipError_t launch_prep(const MetaHeader &h, void *meta_dev, const void *blob_host, size_t blob_bytes, void *zero_dev,
+                       void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt, hipStream_t st)
+{
+    BlobChunk c;
+    std::memset(&c, 0, sizeof(c));
+    std::memcpy(c.w, blob_host, blob_bytes);
+    const bool pack = h.n_adapters > 0 && (want_at || want_ap);
+    const int pack_bx = (int)((h.D + 63) / 64);
+    const int n_pack = pack ? pack_bx * h.n_adapters : 0;
+    const int n_tr = (hf && zt) ? h.n_blocks * (kSkinnyRows / 16) : 0;
+    hipLaunchKernelGGL(k_prep, dim3((unsigned)(1 + n_pack + n_tr)), dim3(256), 0, st, c, static_cast<uint32_t *>(meta_dev),
+                       (int)((blob_bytes + 3) / 4), static_cast<uint32_t *>(zero_dev), static_cast<uint16_t *>(at),
+                       static_cast<uint16_t *>(ap), want_at ? 1 : 0, want_ap ? 1 : 0, pack_bx > 0 ? pack_bx : 1, n_pack, hf,
+                       static_cast<uint16_t *>(zt));
     return hipGetLastError();
 }
 

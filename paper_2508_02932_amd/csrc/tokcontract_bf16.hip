@@ -8,8 +8,8 @@
 // The token index is the slow index of the big matrix, so its MFMA operand needs a transpose; it
 // is staged HBM -> LDS as it lies in memory (direct loads into a ring of stages that fills the LDS)
 // and read with the transposing LDS load (ds_read_b64_tr_b16).  The rank stays whole in every tile;
-// tiles are cut along the hidden dimension (256 columns per workgroup of eight waves, 32 columns
-// per wave) and a workgroup walks the tokens of one adapter, longest adapters first.  The MFMA code
+// tiles are cut along the hidden dimension (256 or 128 columns per workgroup, one wave per 32
+// columns) and a workgroup walks the tokens of one adapter, longest adapters first.  The MFMA code
 // is specialised per number of 16-wide rank blocks so that every LDS read of a stage is in flight
 // before the first MFMA.  Nothing in the loop may spill: a scratch reload waits on the same counter
 // as the direct loads and would drain the ring.
@@ -27,14 +27,11 @@ typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T *)(p))
 
-constexpr int TC_BC = 256;                 // columns of the big matrix per workgroup
 constexpr int TC_BT = 64;                  // tokens per stage (TC_BT / 32 MFMA K steps)
 constexpr int TC_MAX_NST = 8;              // LDS ring stages: as many as fit in the 160 KB of a compute unit, at most this
 constexpr int TC_LDS_BYTES = 160 * 1024;
-constexpr int TC_S_BYTES = TC_BT * TC_BC * 2;             // [TC_BT t][256 c]
-constexpr int TC_NW = 8;                                  // waves per workgroup
-constexpr int TC_SL = TC_S_BYTES / 1024 / TC_NW;          // big-matrix load instructions per wave per stage
-constexpr int TC_CB = TC_BC / 16 / TC_NW;                 // 16-column MFMA blocks per wave
+constexpr int TC_CB = 2;                                  // 16-column MFMA blocks per wave: a wave owns 32 columns
+constexpr int TC_SL = TC_BT * 32 * 2 / 1024;              // big-matrix load instructions per wave per stage (4)
 constexpr int TC_NB = PLORA_MAX_RANK / 16;
 constexpr int TC_KS = TC_BT / 32;                         // MFMA K steps per stage
 constexpr int TC_ZC = TC_BT / 8;                          // 16-byte chunks per small-factor row
@@ -64,11 +61,21 @@ __device__ inline int next_seg_of(const MetaView &mv, int from, int k)
 
 // grid (column tiles, adapters, token splits).  part != nullptr: write the fp32 partial tile
 // [r16][C] of this split instead of the final result.
-template <bool WANT_DA>
-__global__ void __launch_bounds__(64 * TC_NW) k_tokc(MetaView mv, const uint16_t *__restrict__ S, int C,
+template <bool WANT_DA, int BC>
+__global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 2))) k_tokc(MetaView mv, const uint16_t *__restrict__ S, int C,
                                              const uint16_t *__restrict__ zt, const uint16_t *__restrict__ zero,
                                              float *__restrict__ part, int r16_total, int nst)
 {
+    // BC columns of the big matrix per workgroup (256 or 128), one wave per 32 columns
+    static_assert(BC == 256 || BC == 128, "");
+    constexpr int TC_BC = BC, TC_NW = BC / 32, TC_S_BYTES = TC_BT * BC * 2;
+    constexpr int CPRW = BC / 8;                                  // 16-byte chunks per row of the big-matrix tile
+    constexpr int RPIW = 64 / CPRW;                               // rows per 1 KB load instruction
+    // 16-byte chunk c of token row u is stored at slot c ^ swz(u); chosen so that the 8 rows (u..u+3 and
+    // u+8..u+11) that one pass of a transposing read touches fall into 8 different 32-byte bank groups
+    auto swz = [](int u) {
+        return BC == 256 ? 4 * (u & 3) + 2 * ((u >> 3) & 1) : 2 * (u & 3) + 8 * ((u >> 3) & 1);
+    };
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int k = mv.ad[blockIdx.y].by_tokens;       // longest adapters first
     const AdapterInfo a = mv.ad[k];
@@ -109,11 +116,11 @@ __global__ void __launch_bounds__(64 * TC_NW) k_tokc(MetaView mv, const uint16_t
     };
     load_desc();
 
-    // ---- loader.  Big-matrix tile [TC_BT t][32 chunks] (512-byte rows): instruction q covers token rows
-    // 2q, 2q+1, lane -> (row 2q + lane/32, slot lane%32), slot c' of row u holds chunk
-    // c' ^ (4*(u&3) + 2*((u>>3)&1)); wave w issues q = w, w+8, ...  Small-factor tile [r16 j][TC_ZC chunks]:
+    // ---- loader.  Big-matrix tile [TC_BT t][CPRW chunks]: instruction q covers token rows RPIW q ..,
+    // lane -> (row RPIW q + lane / CPRW, slot lane % CPRW); wave w issues q = w, w + TC_NW, ...
+    // Small-factor tile [r16 j][TC_ZC chunks]:
     // instruction q covers rows TC_ZR q.., lane -> (row TC_ZR q + lane/TC_ZC, slot lane%TC_ZC), slot c' of
-    // row u holds chunk c' ^ ((u >> TC_ZSH) & (TC_ZC-1)); wave w issues q = w, w+8 below r16/TC_ZR.
+    // row u holds chunk c' ^ ((u >> TC_ZSH) & (TC_ZC-1)); wave w issues q = w, w + TC_NW, ... below r16/TC_ZR.
     const int nzi = a.r16 / TC_ZR;
     const int my_z = (nzi > wave) ? (nzi - wave + TC_NW - 1) / TC_NW : 0;
     const int lps = TC_SL + my_z;
@@ -126,8 +133,8 @@ __global__ void __launch_bounds__(64 * TC_NW) k_tokc(MetaView mv, const uint16_t
 #pragma unroll
         for (int jj = 0; jj < TC_SL; ++jj) {
             const int q = wave + TC_NW * jj;
-            const int u = q * 2 + (lane >> 5);
-            const int chunk = (lane & 31) ^ (4 * (u & 3) + 2 * ((u >> 3) & 1));
+            const int u = q * RPIW + lane / CPRW;
+            const int chunk = (lane % CPRW) ^ swz(u);
             int c = c0 + chunk * 8;
             c = c < C ? c : C - 8;                                  // columns past the end only feed outputs that are not stored
             const int t = tbase + u;
@@ -135,7 +142,7 @@ __global__ void __launch_bounds__(64 * TC_NW) k_tokc(MetaView mv, const uint16_t
             load16(p, base + q * 1024);
         }
 #pragma unroll
-        for (int jj = 0; jj < 16 / TC_ZR / (TC_NW / 8); ++jj) {
+        for (int jj = 0; jj < (PLORA_MAX_RANK / TC_ZR + TC_NW - 1) / TC_NW; ++jj) {
             if (jj < my_z) {
                 const int q = wave + TC_NW * jj;
                 const int u = q * TC_ZR + lane / TC_ZC;
@@ -156,7 +163,7 @@ __global__ void __launch_bounds__(64 * TC_NW) k_tokc(MetaView mv, const uint16_t
     for (int cb = 0; cb < TC_CB; ++cb) {
         const int u = kg * 8 + (i16 >> 2);                            // token row fetched by this lane (first read)
         const int cl = wave * (TC_CB * 16) + cb * 16 + (i16 & 3) * 4; // first column fetched by this lane
-        soff[cb] = u * (TC_BC * 2) + ((((cl >> 3) ^ (4 * (u & 3) + 2 * ((u >> 3) & 1))) * 16) + (cl & 7) * 2);
+        soff[cb] = u * (TC_BC * 2) + ((((cl >> 3) ^ swz(u)) * 16) + (cl & 7) * 2);
     }
     // second read (token row u+4) and later K steps (u+32): (u&3) and (u>>3)&1 unchanged, plain adds
     // small-factor operand: rank row j = 16b + i16, chunk 4*ks + kg; the swizzle term only depends on
@@ -272,41 +279,77 @@ __global__ void __launch_bounds__(256) k_tokc_finish(MetaView mv, const float *_
     else a.dB[(int64_t)j * C + c] = a.scale * sum;
 }
 
+// Launch shape: column-tile width and number of token splits.  Aim at about two workgroups per
+// compute unit: 256-column tiles when they alone give that many, otherwise 128-column tiles plus a
+// split of the token walk.  The split is capped so that a split keeps about four stages, and so that
+// the fp32 partial tiles (written once, read once) stay below half of the bytes of the big matrix.
+static int tokc_plan(const MetaHeader &h, int64_t C, int n_active_adapters, int *bc_out)
+{
+    int bc = 256, splits = 1;
+    if (n_active_adapters > 0) {
+        const int64_t wgs256 = (C + 255) / 256 * n_active_adapters;
+        if (wgs256 < 400) {
+            bc = 128;
+            const int64_t wgs = (C + 127) / 128 * n_active_adapters;
+            int want = (int)((512 + wgs - 1) / wgs);
+            int cap = (int)(h.T / TC_BT / n_active_adapters / 4);
+            int64_t r16_sum = 0;                                     // upper bound of the partial rows: every adapter at max_r16
+            r16_sum = (int64_t)h.n_adapters * (h.max_r16 > 0 ? h.max_r16 : 16);
+            const int cap_bytes = (int)(h.T / (8 * r16_sum));
+            if (cap > cap_bytes) cap = cap_bytes;
+            if (cap < 1) cap = 1;
+            if (want > cap) want = cap;
+            if (want > kTokMaxSplits) want = kTokMaxSplits;
+            splits = want < 1 ? 1 : want;
+        }
+    }
+    if (bc_out) *bc_out = bc;
+    return splits;
+}
+
 int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters)
 {
-    if (n_active_adapters <= 0) return 1;
-    const int64_t wgs = (C + TC_BC - 1) / TC_BC * n_active_adapters;
-    int want = (int)((1024 + wgs - 1) / wgs);              // two workgroups fit on each of the 256 compute units
-    int cap = (int)(h.T / TC_BT / n_active_adapters / 4);     // keep about four stages per split at least
-    if (cap < 1) cap = 1;
-    if (want > cap) want = cap;
-    if (want > kTokMaxSplits) want = kTokMaxSplits;
-    return want < 1 ? 1 : want;
+    return tokc_plan(h, C, n_active_adapters, nullptr);
+}
+
+template <bool WANT_DA, int BC>
+static hipError_t launch_tokc(const MetaView &mv, const MetaHeader &h, const uint16_t *S, int C, const uint16_t *zt,
+                              const uint16_t *zero, float *part, int n_split, int r16_total, hipStream_t st)
+{
+    // ring depth: the share of the 160 KB of LDS that lets 256 / BC workgroups sit on a compute unit,
+    // but three stages at least
+    const size_t stage = (size_t)TC_BT * BC * 2 + (size_t)(h.max_r16 > 0 ? h.max_r16 : 16) * TC_BT * 2;
+    size_t budget = (size_t)TC_LDS_BYTES * BC / 256;
+    if (budget < 3 * stage) budget = 3 * stage;
+    int nst = (int)(budget / stage);
+    nst = nst > TC_MAX_NST ? TC_MAX_NST : nst;
+    const size_t lds = nst * stage;
+    static size_t allowed = 0;
+    auto kern = k_tokc<WANT_DA, BC>;
+    if (lds > allowed) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        allowed = lds;
+    }
+    const dim3 grid((unsigned)((C + BC - 1) / BC), (unsigned)h.n_adapters, (unsigned)n_split);
+    hipLaunchKernelGGL(kern, grid, dim3(2 * BC), lds, st, mv, S, C, zt, zero, n_split > 1 ? part : nullptr, r16_total, nst);
+    return hipGetLastError();
 }
 
 hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool want_dA, const void *S,
                                    int64_t C, const void *zt, const void *zero, float *part, int n_split,
-                                   int r16_total, hipStream_t st)
+                                   int r16_total, int n_active_adapters, hipStream_t st)
 {
     if (h.n_adapters == 0) return hipSuccess;
-    const size_t stage = TC_S_BYTES + (size_t)(h.max_r16 > 0 ? h.max_r16 : 16) * TC_BT * 2;
-    int nst = (int)(TC_LDS_BYTES / stage);
-    nst = nst > TC_MAX_NST ? TC_MAX_NST : nst;
-    const size_t lds = nst * stage;
-    float *p = n_split > 1 ? part : nullptr;
-    const dim3 grid((unsigned)((C + TC_BC - 1) / TC_BC), (unsigned)h.n_adapters, (unsigned)n_split);
+    int bc = 256;
+    if (tokc_plan(h, C, n_active_adapters, &bc) != n_split) return hipErrorInvalidValue;   // the caller sized `part` from the same plan
     const uint16_t *s16 = static_cast<const uint16_t *>(S), *z16 = static_cast<const uint16_t *>(zt);
     const uint16_t *zero16 = static_cast<const uint16_t *>(zero);
-    static size_t allowed[2] = {0, 0};
-    if (lds > allowed[want_dA ? 1 : 0]) {
-        const void *f = want_dA ? reinterpret_cast<const void *>(k_tokc<true>) : reinterpret_cast<const void *>(k_tokc<false>);
-        hipError_t e = hipFuncSetAttribute(f, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        allowed[want_dA ? 1 : 0] = lds;
-    }
-    if (want_dA) hipLaunchKernelGGL(k_tokc<true>, grid, dim3(64 * TC_NW), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total, nst);
-    else hipLaunchKernelGGL(k_tokc<false>, grid, dim3(64 * TC_NW), lds, st, mv, s16, (int)C, z16, zero16, p, r16_total, nst);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+#define PL_TOKC(DA_, BC_) launch_tokc<DA_, BC_>(mv, h, s16, (int)C, z16, zero16, part, n_split, r16_total, st)
+    if (want_dA) e = bc == 256 ? PL_TOKC(true, 256) : PL_TOKC(true, 128);
+    else e = bc == 256 ? PL_TOKC(false, 256) : PL_TOKC(false, 128);
+#undef PL_TOKC
     if (e != hipSuccess || n_split <= 1) return e;
     const dim3 g2((unsigned)((C + 255) / 256), (unsigned)r16_total);
     if (want_dA) hipLaunchKernelGGL(k_tokc_finish<true>, g2, dim3(256), 0, st, mv, part, (int)C, n_split, r16_total);
