@@ -199,7 +199,7 @@ __global__ void __launch_bounds__(256) k_skinny_finish(MetaView mv, int mode, co
                                                       uint16_t *__restrict__ zt, int zt_scaled)
 {
     constexpr int FR = 16;                            // token rows per workgroup (grid.y slices of a block)
-    __shared__ float tile[FR][PLORA_MAX_RANK + 1];
+    __shared__ float tile[FR * PLORA_MAX_RANK];       // [FR][r16], pitch r16
     const int blk = blockIdx.x;
     const int n_seg = mv.hdr->n_seg;
     int s = 0;
@@ -218,38 +218,35 @@ __global__ void __launch_bounds__(256) k_skinny_finish(MetaView mv, int mode, co
     const int r = g.r, r16 = g.r16;
     const int64_t tile_elems = (int64_t)kSkinnyRows * mv.hdr->max_r16;
     const int64_t split_stride = (int64_t)gridDim.x * tile_elems;
-    const float *src = part + (int64_t)blk * tile_elems + (int64_t)r0 * r16;
-    for (int e = threadIdx.x; e < FR * r16; e += 256) {
-        float v[kSkinnyMaxSplits];
-#pragma unroll
-        for (int sp = 0; sp < kSkinnyMaxSplits; ++sp) v[sp] = (sp < n_split) ? src[sp * split_stride + e] : 0.f;
-        float sum = v[0];
-#pragma unroll
-        for (int sp = 1; sp < kSkinnyMaxSplits; ++sp) sum += v[sp];
-        tile[e / r16][e % r16] = sum;
+    // the FR rows of r16 partial sums are contiguous in every split: flat walk, four floats per thread
+    const float4 *src = reinterpret_cast<const float4 *>(part + (int64_t)blk * tile_elems + (int64_t)r0 * r16);
+    for (int e = threadIdx.x; e < FR * r16 / 4; e += 256) {
+        float4 sum = src[e];
+        for (int sp = 1; sp < n_split; ++sp) {        // fixed order
+            const float4 v = src[sp * (split_stride / 4) + e];
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        reinterpret_cast<float4 *>(tile)[e] = sum;
     }
     __syncthreads();
-    if (hf) {
-        float *dst = hf + g.h_off + (int64_t)t0 * r;
-        for (int e = threadIdx.x; e < nt * r; e += 256) {
-            const float v = tile[e / r][e % r];
-            dst[e] = (mode == 0) ? v : mult * v;
+    // outputs: thread -> (token tt = tid / 16, columns j = tid % 16 + 16 m), or transposed for zt
+    const int hi = threadIdx.x >> 4, lo = threadIdx.x & 15;
+    if (hf && hi < nt) {
+        float *dst = hf + g.h_off + (int64_t)(t0 + hi) * r;
+        for (int j = lo; j < r; j += 16) {
+            const float v = tile[hi * r16 + j];
+            dst[j] = (mode == 0) ? v : mult * v;
         }
     }
-    if (hb) {
-        uint16_t *dst = hb + g.hb_off + (int64_t)t0 * g.rp;
-        for (int e = threadIdx.x; e < nt * g.rp; e += 256) {
-            const int tt = e / g.rp, j = e % g.rp;
-            dst[e] = (j < r) ? bf16_rne(mult * tile[tt][j]) : (uint16_t)0;
-        }
+    if (hb && hi < nt) {
+        uint16_t *dst = hb + g.hb_off + (int64_t)(t0 + hi) * g.rp;
+        for (int j = lo; j < g.rp; j += 16) dst[j] = (j < r) ? bf16_rne(mult * tile[hi * r16 + j]) : (uint16_t)0;
     }
     if (zt) {
         uint16_t *dst = zt + g.zt_off + t0;
         const float zm = zt_scaled ? mult : 1.f;
-        for (int e = threadIdx.x; e < r16 * FR; e += 256) {
-            const int j = e / FR, tt = e % FR;
-            dst[(int64_t)j * g.lp + tt] = (j < r && tt < nt) ? bf16_rne(zm * tile[tt][j]) : (uint16_t)0;
-        }
+        for (int j = hi; j < r16; j += 16)
+            dst[(int64_t)j * g.lp + lo] = (j < r && lo < nt) ? bf16_rne(zm * tile[lo * r16 + j]) : (uint16_t)0;
     }
 }
 

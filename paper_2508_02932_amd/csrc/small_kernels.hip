@@ -54,36 +54,44 @@ hipError_t clear_zero_page(void *zero_dev, hipStream_t st)
 // One block handles 64 rows i of one adapter; the tile goes through LDS so that both the reads of
 // A_k (contiguous in j) and the writes of A_k^T (contiguous in i) are coalesced.
 __device__ inline void pack_block(const AdapterInfo &a, int64_t D, int bx, uint16_t *at, uint16_t *ap, int want_at,
-                                  int want_ap, uint16_t (*tile)[PLORA_MAX_RANK + 2])
+                                  int want_ap, uint16_t *tile)
 {
+    // The 64 rows of A_k handled here are one contiguous slab of 64 r elements: copy it to LDS as it is
+    // (16 bytes per thread and step), then write both layouts from there.
     const int64_t i0 = (int64_t)bx * 64;
-    const uint16_t *A = static_cast<const uint16_t *>(a.A);
     const int r = a.r;
     const int rows = (int)((D - i0 < 64) ? D - i0 : 64);
-    for (int e = threadIdx.x; e < rows * r; e += 256) {
-        const int ii = e / r, j = e % r;
-        tile[ii][j] = A[(i0 + ii) * r + j];
-    }
+    const uint4 *src = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.A) + i0 * r);
+    const int n_vec = rows * r / 8;                    // r * 2 bytes * rows is a multiple of 16 when rows == 64
+    for (int v = threadIdx.x; v < n_vec; v += 256) reinterpret_cast<uint4 *>(tile)[v] = src[v];
+    for (int e = n_vec * 8 + threadIdx.x; e < rows * r; e += 256)
+        tile[e] = static_cast<const uint16_t *>(a.A)[i0 * r + e];
     __syncthreads();
     if (want_at) {
+        // A_k^T rows j: 64 consecutive elements each; a wave writes one row segment of 128 bytes
         uint16_t *dst = at + a.at_off;
-        for (int e = threadIdx.x; e < a.r16 * 64; e += 256) {
-            const int j = e / 64, ii = e % 64;
-            if (ii < rows) dst[(int64_t)j * D + i0 + ii] = (j < r) ? tile[ii][j] : (uint16_t)0;
-        }
+        const int ii = threadIdx.x & 63;
+        for (int j = threadIdx.x >> 6; j < a.r16; j += 4)
+            if (ii < rows) dst[(int64_t)j * D + i0 + ii] = (j < r) ? tile[ii * r + j] : (uint16_t)0;
     }
     if (want_ap) {
-        uint16_t *dst = ap + a.ap_off;
-        for (int e = threadIdx.x; e < 64 * a.rp; e += 256) {
-            const int ii = e / a.rp, j = e % a.rp;
-            if (ii < rows) dst[(i0 + ii) * a.rp + j] = (j < r) ? tile[ii][j] : (uint16_t)0;
-        }
+        // padded A_k: rows of rp elements, 8 elements (16 bytes) per thread and step
+        uint16_t *dst = ap + a.ap_off + i0 * a.rp;
+        const int vec_per_row = a.rp / 8, lanes_per_row = 8;         // rp is a multiple of 64
+        const int ii0 = threadIdx.x / lanes_per_row, l = threadIdx.x % lanes_per_row;
+        for (int ii = ii0; ii < rows; ii += 256 / lanes_per_row)
+            for (int v = l; v < vec_per_row; v += lanes_per_row) {
+                union { uint4 q; uint16_t h[8]; } u;
+#pragma unroll
+                for (int t = 0; t < 8; ++t) { const int j = v * 8 + t; u.h[t] = (j < r) ? tile[ii * r + j] : (uint16_t)0; }
+                reinterpret_cast<uint4 *>(dst + (int64_t)ii * a.rp)[v] = u.q;
+            }
     }
 }
 
 __global__ void __launch_bounds__(256) k_pack_a(MetaView mv, uint16_t *at, uint16_t *ap, int want_at, int want_ap)
 {
-    __shared__ uint16_t tile[64][PLORA_MAX_RANK + 2];
+    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * PLORA_MAX_RANK];
     const AdapterInfo a = mv.ad[blockIdx.y];
     pack_block(a, mv.hdr->D, blockIdx.x, at, ap, want_at, want_ap, tile);
 }
@@ -108,27 +116,26 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
 
 // zt[j][t] = bf16(h[t][j]); rows j >= r and the padding tokens are written as zero.  Grid: (token
 // block of kSkinnyRows rows, slice of 16 rows inside it).
-__device__ inline void h_to_zt_slice(const SegInfo &g, int blk, int slice, const float *hf, uint16_t *zt,
-                                     float (*tile)[PLORA_MAX_RANK + 1])
+__device__ inline void h_to_zt_slice(const SegInfo &g, int blk, int slice, const float *hf, uint16_t *zt, float *tile)
 {
     constexpr int FR = 16;
     const int t0 = (blk - g.blk0) * kSkinnyRows + slice * FR;   // first token of the slice inside the segment
     if (t0 >= g.lp) return;
     int nt = g.row1 - g.row0 - t0;
     nt = nt < 0 ? 0 : (nt < FR ? nt : FR);
+    // the nt rows of r floats are contiguous: flat copy, then transposed reads (thread -> rank row j, token tt)
     const float *src = hf + g.h_off + (int64_t)t0 * g.r;
-    for (int e = threadIdx.x; e < nt * g.r; e += 256) tile[e / g.r][e % g.r] = src[e];
+    for (int e = threadIdx.x; e < nt * g.r; e += 256) tile[e] = src[e];
     __syncthreads();
     uint16_t *dst = zt + g.zt_off + t0;
-    for (int e = threadIdx.x; e < g.r16 * FR; e += 256) {
-        const int j = e / FR, tt = e % FR;
-        dst[(int64_t)j * g.lp + tt] = (j < g.r && tt < nt) ? f32_to_bf16_rne(tile[tt][j]) : (uint16_t)0;
-    }
+    const int tt = threadIdx.x & 15;
+    for (int j = threadIdx.x >> 4; j < g.r16; j += 16)
+        dst[(int64_t)j * g.lp + tt] = (j < g.r && tt < nt) ? f32_to_bf16_rne(tile[tt * g.r + j]) : (uint16_t)0;
 }
 
 __global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, uint16_t *zt)
 {
-    __shared__ float tile[16][PLORA_MAX_RANK + 1];
+    __shared__ float tile[16 * PLORA_MAX_RANK];
     const int blk = blockIdx.x;
     const int n_seg = mv.hdr->n_seg;
     int s = 0;
@@ -166,9 +173,9 @@ __global__ void __launch_bounds__(256) k_prep(BlobChunk c, uint32_t *meta_dst, i
                                              uint16_t *at, uint16_t *ap, int want_at, int want_ap, int pack_bx,
                                              int n_pack, const float *hf, uint16_t *zt)
 {
-    __shared__ union {
-        uint16_t pack[64][PLORA_MAX_RANK + 2];
-        float tr[16][PLORA_MAX_RANK + 1];
+    __shared__ __attribute__((aligned(16))) union {
+        uint16_t pack[64 * PLORA_MAX_RANK];
+        float tr[16 * PLORA_MAX_RANK];
     } sh;
     int b = blockIdx.x;
     if (b == 0) {
