@@ -34,12 +34,13 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BM = 256, BN = 256;
 
+// two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 {
-    uint32_t a = __float_as_uint(lo), b = __float_as_uint(hi);
-    a += 0x7FFFu + ((a >> 16) & 1u);
-    b += 0x7FFFu + ((b >> 16) & 1u);
-    return (a >> 16) | (b & 0xFFFF0000u);
+    typedef __bf16 v2bf __attribute__((ext_vector_type(2)));
+    typedef float v2f __attribute__((ext_vector_type(2)));
+    const v2f f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));
 }
 
 // Next segment at or after `from` that overlaps rows [m0, m1), has an adapter and at least one row.
@@ -71,6 +72,7 @@ constexpr int NL = 4;                        // load instructions (1 KB each) pe
 constexpr int kGemmGrid = 256;               // persistent grid: one workgroup per compute unit of an MI355X
 static_assert(kRankPadGemm % BK == 0, "extension steps must be whole stages");
 static_assert(KS == 4 && BM == 256 && BN == 256, "the schedule below is written for this tile");
+static_assert(BM == kGemmTileRows && BK == kRankPadGemm, "the per-tile extension table is built for this tile");
 
 __device__ inline void wait_vmcnt_048(int n)
 {
@@ -90,7 +92,6 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
     const int Kd = (int)(FWD ? mv.hdr->D : mv.hdr->K);
     const int N = (int)(FWD ? mv.hdr->K : mv.hdr->D);
     const int ldw = (int)mv.hdr->K;
-    const int n_seg = mv.hdr->n_seg;
 
     // ---- workgroup -> tiles.  The grid is persistent (one workgroup per compute unit, each walks the
     // tile ids b, b + grid, b + 2 grid, ...).  Workgroups are dealt round-robin to the 8 XCDs (each with
@@ -161,12 +162,10 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
     const int nk_main = (Kd + BK - 1) / BK;
     int ext_seg = 0, ext_kk = 0, n_it = 0;
     auto scan_segments = [&]() {
-        ext_seg = next_ext_seg(mv, 0, m0, m1);
+        const TileExt te = mv.tile_ext[m0 / BM];   // built on the host: one load instead of a walk over the segments
+        ext_seg = te.first_seg;
         ext_kk = 0;
-        int n_ext = 0;
-        for (int s = ext_seg; s < n_seg; s = next_ext_seg(mv, s + 1, m0, m1))
-            n_ext += mv.seg[s].rp / BK;
-        n_it = nk_main + n_ext;
+        n_it = nk_main + te.n_ext;
     };
 
     // The direct-to-LDS loads are issued through inline assembly: the compiler, which cannot tell

@@ -39,6 +39,8 @@ struct HostMeta {
     MetaHeader hdr;
     std::vector<SegInfo> seg;
     std::vector<AdapterInfo> ad;
+    std::vector<TileExt> tile_ext;
+    std::vector<int32_t> blk_seg;
     WorkspaceLayout ws;
     size_t h_elems = 0, hb_elems = 0, zt_elems = 0, at_elems = 0, ap_elems = 0;
     int r16_total = 0, n_active = 0, split_dA = 1, split_dB = 1;
@@ -87,6 +89,25 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     }
     m.hdr.n_blocks = blk;
     m.r16_total = r16_off;
+    m.blk_seg.assign(blk, 0);
+    for (int32_t s = 0; s < d->n_seg; ++s) {
+        const SegInfo &g = m.seg[s];
+        if (g.adapter < 0) continue;
+        const int32_t nb = (g.row1 - g.row0 + kSkinnyRows - 1) / kSkinnyRows;
+        for (int32_t b = 0; b < nb; ++b) m.blk_seg[g.blk0 + b] = s;
+    }
+    {
+        const int64_t tiles = (d->T + kGemmTileRows - 1) / kGemmTileRows;
+        m.tile_ext.assign((size_t)tiles, TileExt{d->n_seg, 0});
+        for (int32_t s = 0; s < d->n_seg; ++s) {
+            const SegInfo &g = m.seg[s];
+            if (g.adapter < 0 || g.row1 <= g.row0) continue;
+            for (int64_t t = g.row0 / kGemmTileRows; t <= (g.row1 - 1) / kGemmTileRows; ++t) {
+                if (m.tile_ext[t].first_seg == d->n_seg) m.tile_ext[t].first_seg = s;
+                m.tile_ext[t].n_ext += g.rp / kRankPadGemm;
+            }
+        }
+    }
     {
         std::vector<char> seen(d->n_adapters, 0);
         for (int32_t s = 0; s < d->n_seg; ++s)
@@ -112,7 +133,8 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     WorkspaceLayout &w = m.ws;
     size_t o = 0;
     w.zero = o; o += kZeroBytes;
-    w.meta_bytes = sizeof(MetaHeader) + m.seg.size() * sizeof(SegInfo) + m.ad.size() * sizeof(AdapterInfo);
+    w.meta_bytes = sizeof(MetaHeader) + m.seg.size() * sizeof(SegInfo) + m.ad.size() * sizeof(AdapterInfo) +
+                   m.tile_ext.size() * sizeof(TileExt) + m.blk_seg.size() * sizeof(int32_t);
     w.meta = o; o = align_up(o + w.meta_bytes, 256);
     const bool bf = d->dtype == PLORA_BF16;
     w.at = o;   o = align_up(o + (bf ? m.at_elems * 2 : 0), 256);
@@ -190,10 +212,17 @@ static void build_blob(const HostMeta &m, char *ws, std::vector<char> &blob, Met
     if (!m.seg.empty()) std::memcpy(p, m.seg.data(), m.seg.size() * sizeof(SegInfo));
     p += m.seg.size() * sizeof(SegInfo);
     if (!m.ad.empty()) std::memcpy(p, m.ad.data(), m.ad.size() * sizeof(AdapterInfo));
+    p += m.ad.size() * sizeof(AdapterInfo);
+    if (!m.tile_ext.empty()) std::memcpy(p, m.tile_ext.data(), m.tile_ext.size() * sizeof(TileExt));
+    p += m.tile_ext.size() * sizeof(TileExt);
+    if (!m.blk_seg.empty()) std::memcpy(p, m.blk_seg.data(), m.blk_seg.size() * sizeof(int32_t));
     char *dev = ws + m.ws.meta;
-    mv.hdr = reinterpret_cast<const MetaHeader *>(dev);
-    mv.seg = reinterpret_cast<const SegInfo *>(dev + sizeof(MetaHeader));
-    mv.ad = reinterpret_cast<const AdapterInfo *>(dev + sizeof(MetaHeader) + m.seg.size() * sizeof(SegInfo));
+    size_t off = 0;
+    mv.hdr = reinterpret_cast<const MetaHeader *>(dev); off += sizeof(MetaHeader);
+    mv.seg = reinterpret_cast<const SegInfo *>(dev + off); off += m.seg.size() * sizeof(SegInfo);
+    mv.ad = reinterpret_cast<const AdapterInfo *>(dev + off); off += m.ad.size() * sizeof(AdapterInfo);
+    mv.tile_ext = reinterpret_cast<const TileExt *>(dev + off); off += m.tile_ext.size() * sizeof(TileExt);
+    mv.blk_seg = reinterpret_cast<const int32_t *>(dev + off);
 }
 
 // The small jobs in front of the heavy kernels: metadata blob and zero page into the workspace,

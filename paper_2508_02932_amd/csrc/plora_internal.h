@@ -53,11 +53,21 @@ struct MetaHeader {
     int32_t max_r16;      // largest rank (padded to 16) among segments with tokens
 };
 
-// Device view of the metadata blob (all pointers into the workspace).
+// One entry per 256-row tile of the base GEMMs: the low-rank extension steps of that tile.
+constexpr int kGemmTileRows = 256;
+struct TileExt {
+    int32_t first_seg;    // first segment with an adapter and rows that overlaps the tile (n_seg if none)
+    int32_t n_ext;        // extension steps of the tile: sum over such segments of rp / 64
+};
+
+// Device view of the metadata blob (all pointers into the workspace).  Blob layout: header, seg[n_seg],
+// ad[n_adapters], tile_ext[ceil(T / 256)], blk_seg[n_blocks].
 struct MetaView {
     const MetaHeader *hdr;
     const SegInfo *seg;
     const AdapterInfo *ad;
+    const TileExt *tile_ext;
+    const int32_t *blk_seg;   // segment of each token block of kSkinnyRows rows
 };
 
 // Byte offsets of the workspace regions, each 256-byte aligned.

@@ -57,13 +57,7 @@ __global__ void __launch_bounds__(256) k_skinny(MetaView mv, int mode, const uin
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int blk = blockIdx.x;
-    const int n_seg = mv.hdr->n_seg;
-    int s = 0;
-    for (int q = 0; q < n_seg; ++q) {
-        const SegInfo gq = mv.seg[q];
-        if (gq.adapter >= 0 && gq.row1 > gq.row0 && blk >= gq.blk0) s = q;
-    }
-    const SegInfo g = mv.seg[s];
+    const SegInfo g = mv.seg[mv.blk_seg[blk]];
     const AdapterInfo a = mv.ad[g.adapter];
     const int t0 = (blk - g.blk0) * kSkinnyRows;
     const int nt = (g.row1 - g.row0 - t0 < kSkinnyRows) ? g.row1 - g.row0 - t0 : kSkinnyRows;
@@ -201,13 +195,7 @@ __global__ void __launch_bounds__(256) k_skinny_finish(MetaView mv, int mode, co
     constexpr int FR = 16;                            // token rows per workgroup (grid.y slices of a block)
     __shared__ float tile[FR * PLORA_MAX_RANK];       // [FR][r16], pitch r16
     const int blk = blockIdx.x;
-    const int n_seg = mv.hdr->n_seg;
-    int s = 0;
-    for (int q = 0; q < n_seg; ++q) {
-        const SegInfo gq = mv.seg[q];
-        if (gq.adapter >= 0 && gq.row1 > gq.row0 && blk >= gq.blk0) s = q;
-    }
-    const SegInfo g = mv.seg[s];
+    const SegInfo g = mv.seg[mv.blk_seg[blk]];
     const float mult = mv.ad[g.adapter].scale;
     const int tb = (blk - g.blk0) * kSkinnyRows;      // first token of the block inside the segment
     const int r0 = blockIdx.y * FR;                   // first row of this slice inside the block

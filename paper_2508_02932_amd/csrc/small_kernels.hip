@@ -137,13 +137,7 @@ __global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, u
 {
     __shared__ float tile[16 * PLORA_MAX_RANK];
     const int blk = blockIdx.x;
-    const int n_seg = mv.hdr->n_seg;
-    int s = 0;
-    for (int q = 0; q < n_seg; ++q) {
-        const SegInfo g = mv.seg[q];
-        if (g.adapter >= 0 && g.row1 > g.row0 && blk >= g.blk0) s = q;
-    }
-    const SegInfo g = mv.seg[s];
+    const SegInfo g = mv.seg[mv.blk_seg[blk]];
     h_to_zt_slice(g, blk, blockIdx.y, hf, zt, tile);
 }
 
@@ -194,11 +188,9 @@ __global__ void __launch_bounds__(256) k_prep(BlobChunk c, uint32_t *meta_dst, i
     }
     b -= n_pack;
     const int blk = b / (kSkinnyRows / 16), slice = b % (kSkinnyRows / 16);
-    int s = 0;
-    for (int q = 0; q < hdr.n_seg; ++q) {
-        const SegInfo g = read_arg<SegInfo>(c, seg_base + q * (int)sizeof(SegInfo));
-        if (g.adapter >= 0 && g.row1 > g.row0 && blk >= g.blk0) s = q;
-    }
+    const int tiles = (int)((hdr.T + kGemmTileRows - 1) / kGemmTileRows);
+    const int blk_base = ad_base + hdr.n_adapters * (int)sizeof(AdapterInfo) + tiles * (int)sizeof(TileExt);
+    const int s = (int)c.w[blk_base / 4 + blk];
     const SegInfo g = read_arg<SegInfo>(c, seg_base + s * (int)sizeof(SegInfo));
     h_to_zt_slice(g, blk, slice, hf, zt, sh.tr);
 }
