@@ -40,7 +40,7 @@ struct HostMeta {
     std::vector<SegInfo> seg;
     std::vector<AdapterInfo> ad;
     std::vector<TileExt> tile_ext;
-    std::vector<int32_t> blk_seg;
+    std::vector<int32_t> blk_seg, seg_list;
     WorkspaceLayout ws;
     size_t h_elems = 0, hb_elems = 0, zt_elems = 0, at_elems = 0, ap_elems = 0;
     int r16_total = 0, n_active = 0, split_dA = 1, split_dB = 1;
@@ -96,6 +96,13 @@ static void build_meta(const plora_desc *d, HostMeta &m)
         const int32_t nb = (g.row1 - g.row0 + kSkinnyRows - 1) / kSkinnyRows;
         for (int32_t b = 0; b < nb; ++b) m.blk_seg[g.blk0 + b] = s;
     }
+    m.seg_list.clear();
+    for (int32_t k = 0; k < d->n_adapters; ++k) {
+        m.ad[k].seg_list0 = (int32_t)m.seg_list.size();
+        for (int32_t s = 0; s < d->n_seg; ++s)
+            if (m.seg[s].adapter == k && m.seg[s].row1 > m.seg[s].row0) m.seg_list.push_back(s);
+        m.ad[k].n_own = (int32_t)m.seg_list.size() - m.ad[k].seg_list0;
+    }
     {
         const int64_t tiles = (d->T + kGemmTileRows - 1) / kGemmTileRows;
         m.tile_ext.assign((size_t)tiles, TileExt{d->n_seg, 0});
@@ -134,7 +141,7 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     size_t o = 0;
     w.zero = o; o += kZeroBytes;
     w.meta_bytes = sizeof(MetaHeader) + m.seg.size() * sizeof(SegInfo) + m.ad.size() * sizeof(AdapterInfo) +
-                   m.tile_ext.size() * sizeof(TileExt) + m.blk_seg.size() * sizeof(int32_t);
+                   m.tile_ext.size() * sizeof(TileExt) + (m.blk_seg.size() + m.seg_list.size()) * sizeof(int32_t);
     w.meta = o; o = align_up(o + w.meta_bytes, 256);
     const bool bf = d->dtype == PLORA_BF16;
     w.at = o;   o = align_up(o + (bf ? m.at_elems * 2 : 0), 256);
@@ -216,13 +223,16 @@ static void build_blob(const HostMeta &m, char *ws, std::vector<char> &blob, Met
     if (!m.tile_ext.empty()) std::memcpy(p, m.tile_ext.data(), m.tile_ext.size() * sizeof(TileExt));
     p += m.tile_ext.size() * sizeof(TileExt);
     if (!m.blk_seg.empty()) std::memcpy(p, m.blk_seg.data(), m.blk_seg.size() * sizeof(int32_t));
+    p += m.blk_seg.size() * sizeof(int32_t);
+    if (!m.seg_list.empty()) std::memcpy(p, m.seg_list.data(), m.seg_list.size() * sizeof(int32_t));
     char *dev = ws + m.ws.meta;
     size_t off = 0;
     mv.hdr = reinterpret_cast<const MetaHeader *>(dev); off += sizeof(MetaHeader);
     mv.seg = reinterpret_cast<const SegInfo *>(dev + off); off += m.seg.size() * sizeof(SegInfo);
     mv.ad = reinterpret_cast<const AdapterInfo *>(dev + off); off += m.ad.size() * sizeof(AdapterInfo);
     mv.tile_ext = reinterpret_cast<const TileExt *>(dev + off); off += m.tile_ext.size() * sizeof(TileExt);
-    mv.blk_seg = reinterpret_cast<const int32_t *>(dev + off);
+    mv.blk_seg = reinterpret_cast<const int32_t *>(dev + off); off += m.blk_seg.size() * sizeof(int32_t);
+    mv.seg_list = reinterpret_cast<const int32_t *>(dev + off);
 }
 
 // The small jobs in front of the heavy kernels: metadata blob and zero page into the workspace,

@@ -44,6 +44,8 @@ struct AdapterInfo {
     int64_t ap_off;       // element offset of A    [d_in][rp]   in the padded-A buffer
     int32_t r16_off;      // sum of r16 over the adapters before this one (row offset in dA / dB partial tiles)
     int32_t by_tokens;    // entry i: the adapter with the i-th largest token count (ties by index)
+    int32_t seg_list0;    // this adapter's non-empty segments: seg_list[seg_list0 .. seg_list0 + n_own), in segment order
+    int32_t n_own;
 };
 
 struct MetaHeader {
@@ -61,13 +63,14 @@ struct TileExt {
 };
 
 // Device view of the metadata blob (all pointers into the workspace).  Blob layout: header, seg[n_seg],
-// ad[n_adapters], tile_ext[ceil(T / 256)], blk_seg[n_blocks].
+// ad[n_adapters], tile_ext[ceil(T / 256)], blk_seg[n_blocks], seg_list[non-empty segments with an adapter].
 struct MetaView {
     const MetaHeader *hdr;
     const SegInfo *seg;
     const AdapterInfo *ad;
     const TileExt *tile_ext;
     const int32_t *blk_seg;   // segment of each token block of kSkinnyRows rows
+    const int32_t *seg_list;  // non-empty segments grouped by adapter (see AdapterInfo)
 };
 
 // Byte offsets of the workspace regions, each 256-byte aligned.

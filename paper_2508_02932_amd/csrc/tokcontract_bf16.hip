@@ -51,14 +51,6 @@ __device__ inline void tc_wait_vmcnt(int n)
 #undef W_
 }
 
-__device__ inline int next_seg_of(const MetaView &mv, int from, int k)
-{
-    const int n = mv.hdr->n_seg;
-    for (int s = from; s < n; ++s)
-        if (mv.seg[s].adapter == k && mv.seg[s].row1 > mv.seg[s].row0) return s;
-    return n;
-}
-
 // grid (column tiles, adapters, token splits).  part != nullptr: write the fp32 partial tile
 // [r16][C] of this split instead of the final result.
 template <bool WANT_DA, int BC>
@@ -80,37 +72,42 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
     const int k = mv.ad[blockIdx.y].by_tokens;       // longest adapters first
     const AdapterInfo a = mv.ad[k];
     const int c0 = blockIdx.x * TC_BC;
-    const int n_seg = mv.hdr->n_seg;
     const int nb = a.r16 / 16;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
     const int stage_bytes = TC_S_BYTES + mv.hdr->max_r16 * TC_BT * 2;
 
-    // steps (TC_BT tokens each) of this adapter, and the slice of them that belongs to this split
+    // steps (TC_BT tokens each) of this adapter over its own segments (list built on the host), and the
+    // slice of them that belongs to this split
+    const int32_t *own = mv.seg_list + a.seg_list0;
+    const int n_own = a.n_own;
     int n_steps_all = 0;
-    for (int s = next_seg_of(mv, 0, k); s < n_seg; s = next_seg_of(mv, s + 1, k))
-        n_steps_all += (mv.seg[s].row1 - mv.seg[s].row0 + TC_BT - 1) / TC_BT;
+    for (int li = 0; li < n_own; ++li) {
+        const SegInfo g = mv.seg[own[li]];
+        n_steps_all += (g.row1 - g.row0 + TC_BT - 1) / TC_BT;
+    }
     const int per = (n_steps_all + gridDim.z - 1) / gridDim.z;
     const int step0 = blockIdx.z * per;
     int n_steps = n_steps_all - step0;
     n_steps = n_steps < per ? n_steps : per;
     if (n_steps < 0) n_steps = 0;
 
-    // cursor of the next stage to fetch: segment index, token offset inside it, and the fields of that
-    // segment that the loader needs (kept in registers so that the load issue right behind the barrier
-    // does not wait for a metadata fetch)
-    int cur_seg = next_seg_of(mv, 0, k), cur_t = 0;
-    for (int skip = step0; skip > 0 && cur_seg < n_seg;) {
-        const int st_here = (mv.seg[cur_seg].row1 - mv.seg[cur_seg].row0 + TC_BT - 1) / TC_BT;
-        if (skip >= st_here) { skip -= st_here; cur_seg = next_seg_of(mv, cur_seg + 1, k); }
+    // cursor of the next stage to fetch: index into the adapter's segment list, token offset inside that
+    // segment, and the fields of the segment that the loader needs (kept in registers so that the load
+    // issue right behind the barrier does not wait for a metadata fetch)
+    int cur_li = 0, cur_t = 0;
+    for (int skip = step0; skip > 0 && cur_li < n_own;) {
+        const SegInfo g = mv.seg[own[cur_li]];
+        const int st_here = (g.row1 - g.row0 + TC_BT - 1) / TC_BT;
+        if (skip >= st_here) { skip -= st_here; ++cur_li; }
         else { cur_t = skip * TC_BT; skip = 0; }
     }
     int seg_row0 = 0, seg_len = 0, seg_lp = 0;
     int64_t seg_zt = 0;
     auto load_desc = [&]() {
-        if (cur_seg < n_seg) {
-            const SegInfo g = mv.seg[cur_seg];
+        if (cur_li < n_own) {
+            const SegInfo g = mv.seg[own[cur_li]];
             seg_row0 = g.row0; seg_len = g.row1 - g.row0; seg_lp = g.lp; seg_zt = g.zt_off;
         }
     };
@@ -151,7 +148,7 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
             }
         }
         cur_t = tbase + TC_BT;
-        if (cur_t >= seg_len) { cur_seg = next_seg_of(mv, cur_seg + 1, k); cur_t = 0; load_desc(); }
+        if (cur_t >= seg_len) { ++cur_li; cur_t = 0; load_desc(); }
     };
 
     // ---- MFMA operands.  Wave w owns columns 32w..32w+31 (two 16-column blocks) and every rank block.
