@@ -163,3 +163,23 @@ def test_config4_sampled(which):
 @pytest.mark.parametrize("which", [0, 1], ids=["attn", "mlp_up"])
 def test_config5_sampled(which):
     check_sampled_and_adjoint(wl.config(5)[which])
+
+
+def test_odd_shapes_many_tiles():
+    """More GEMM tiles than workgroups of the persistent grid (18 x 18 of them, a count that the XCD
+    remap does not divide), ragged in every dimension: rows, columns and contraction length are no
+    multiples of the tile, segments of unequal length with a base-only one and an adapter that owns
+    two segments, ranks from 1 to 128.  The narrow hidden sizes also send dA and dB through the
+    128-column tiles with a split token walk."""
+    lin = wl.small("odd_many_tiles", "bf16", 1096, 4360,
+                   lengths=[611, 1290, 3, 0, 977, 258, 1031, 307],
+                   seg_adapter=[0, 1, 2, 3, -1, 4, 1, 5],
+                   ranks=[128, 1, 24, 8, 72, 33], scales=[2.0, 0.5, 1.0, 4.0, 2.0, 0.25], seed=83)
+    assert ((lin.layout.T + 255) // 256) * ((lin.K + 255) // 256) > 256
+    check_sampled_and_adjoint(lin)
+    # and with the roles of the hidden sizes swapped (wide contraction, narrow output)
+    lin = wl.small("odd_many_tiles_T", "bf16", 4360, 1096,
+                   lengths=[611, 1290, 3, 0, 977, 258, 1031, 307],
+                   seg_adapter=[0, 1, 2, 3, -1, 4, 1, 5],
+                   ranks=[128, 1, 24, 8, 72, 33], scales=[2.0, 0.5, 1.0, 4.0, 2.0, 0.25], seed=89)
+    check_sampled_and_adjoint(lin)
