@@ -33,6 +33,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default: the headline one)")
     ap.add_argument("--linear", type=int, default=0, help="which linear of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-sequential", action="store_true",
+                    help="skip the context leg that runs the same step one adapter per call")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling this script)")
@@ -94,6 +96,47 @@ def main():
         ms, n = plora.plora_kernel_time(name)
         kern[name] = (ms / n) if n else None
     plora.plora_set_kernel_timing(False)
+
+    # context leg (not the metric): the same work issued one adapter at a time, i.e. one forward and one
+    # backward call per adapter on its own rows with a single-segment description - the launch pattern
+    # that packing replaces (the paper's kernel tables compare against it)
+    sequential = None
+    if not args.no_sequential and lay.n_adapters > 0 and all(int(a) >= 0 for a in lay.seg_adapter) \
+            and len(set(int(a) for a in lay.seg_adapter)) == lay.n_seg:
+        subs = []
+        h_off = 0
+        for sidx in range(lay.n_seg):
+            k = int(lay.seg_adapter[sidx])
+            lo, hi = int(lay.seg_off[sidx]), int(lay.seg_off[sidx + 1])
+            L = hi - lo
+            if L == 0:
+                continue
+            d = plora.Desc(L, D, K, np.array([0, L]), np.array([0]), np.array([lay.rank[k]]),
+                           np.array([lay.scale[k]]), dp.desc.dtype)
+            assert plora.plora_workspace_bytes(d) <= dp.ws.numel()
+            n_h = L * int(lay.rank[k])
+            subs.append((d, dp.x[lo:hi], dp.y[lo:hi], dp.dy[lo:hi], dp.dx[lo:hi], [dp.A[k]], [dp.B[k]],
+                         [dp.dA[k]], [dp.dB[k]], dp.h[h_off:h_off + n_h]))
+            h_off += n_h
+
+        def seq_step():
+            for d, x_, y_, dy_, dx_, A_, B_, dA_, dB_, h_ in subs:
+                plora.plora_linear_fwd(d, x_, dp.W, A_, B_, y_, h_, dp.ws)
+            for d, x_, y_, dy_, dx_, A_, B_, dA_, dB_, h_ in subs:
+                plora.plora_linear_bwd(d, x_, dp.W, A_, B_, dy_, h_, dx_, dA_, dB_, dp.ws)
+
+        n_seq = max(5, args.steps // 2)
+        for _ in range(3):
+            seq_step()
+        torch.cuda.synchronize()
+        t0s = time.perf_counter()
+        for _ in range(n_seq):
+            seq_step()
+        torch.cuda.synchronize()
+        seq_ms = (time.perf_counter() - t0s) * 1e3 / n_seq
+        sequential = {"ms_per_step": round(seq_ms, 4), "steps": n_seq, "calls_per_step": 2 * len(subs),
+                      "packed_speedup": round(seq_ms / ms_per_step, 3),
+                      "note": "same library, one forward and one backward call per adapter on its own rows"}
 
     # algorithmic work per launch of each kernel (true ranks, nothing padded)
     alg = {
@@ -194,6 +237,7 @@ def main():
         "frac_of_bf16_mfma_peak": round(flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
         "roofline": roofline,
         "kernels": kernels,
+        "sequential_adapters": sequential,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
