@@ -86,6 +86,17 @@ def main():
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
 
+    # spread of single steps (context; the metric above is the mean of the timed region): one event pair per step
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for a, b in evs:
+        a.record()
+        step()
+        b.record()
+    torch.cuda.synchronize()
+    per_step = sorted(a.elapsed_time(b) for a, b in evs)
+    step_stats = {"median_ms": round(per_step[len(per_step) // 2], 4), "min_ms": round(per_step[0], 4),
+                  "max_ms": round(per_step[-1], 4)}
+
     # second pass of the same steps with every kernel bracketed by HIP events on its stream
     plora.plora_set_kernel_timing(True)
     for _ in range(args.steps):
@@ -228,6 +239,7 @@ def main():
         "tokens_per_s": round(T / (ms_per_step * 1e-3), 1),
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "step_ms": step_stats,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if lin.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config} / {lin.name}: d_in={D} d_out={K} T={T} "
