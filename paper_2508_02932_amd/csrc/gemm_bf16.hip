@@ -85,13 +85,13 @@ template <bool FWD>
 __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__restrict__ S,
                                               const uint16_t *__restrict__ W, const uint16_t *__restrict__ side,
                                               const uint16_t *__restrict__ ap, const uint16_t *__restrict__ zero,
-                                              uint16_t *__restrict__ Cout, int tiles_m, int tiles_n)
+                                              uint16_t *__restrict__ Cout, int tiles_m, int tiles_n, int M, int d_in, int d_out)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
-    const int M = (int)mv.hdr->T;
-    const int Kd = (int)(FWD ? mv.hdr->D : mv.hdr->K);
-    const int N = (int)(FWD ? mv.hdr->K : mv.hdr->D);
-    const int ldw = (int)mv.hdr->K;
+    // shapes come as kernel arguments, so the first loads do not wait for a metadata fetch
+    const int Kd = FWD ? d_in : d_out;
+    const int N = FWD ? d_out : d_in;
+    const int ldw = d_out;
 
     // ---- workgroup -> tiles.  The grid is persistent (one workgroup per compute unit, each walks the
     // tile ids b, b + grid, b + 2 grid, ...).  Workgroups are dealt round-robin to the 8 XCDs (each with
@@ -484,7 +484,8 @@ static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, const 
     hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < kGemmGrid ? n_tiles : kGemmGrid)), dim3(512), kGemmLds, st, mv,
                        static_cast<const uint16_t *>(S), static_cast<const uint16_t *>(W),
                        static_cast<const uint16_t *>(side), static_cast<const uint16_t *>(ap),
-                       static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n);
+                       static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n, (int)h.T, (int)h.D,
+                       (int)h.K);
     return hipGetLastError();
 }
 
