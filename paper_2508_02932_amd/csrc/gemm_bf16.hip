@@ -69,7 +69,6 @@ constexpr int kXL = 0, kXT = 2 * GR, kWA = 4 * GR, kWB = 7 * GR;   // rings: 2 +
 constexpr int kGemmLds = 10 * GR;            // all 160 KB of a compute unit
 constexpr int WN = 2;                        // 32-column blocks per wave: 8 waves of 128 x 64 outputs
 constexpr int NL = 4;                        // load instructions (1 KB each) per wave per granule
-constexpr int kGemmGrid = 256;               // persistent grid: one workgroup per compute unit of an MI355X
 static_assert(kRankPadGemm % BK == 0, "extension steps must be whole stages");
 static_assert(KS == 4 && BM == 256 && BN == 256, "the schedule below is written for this tile");
 static_assert(BM == kGemmTileRows && BK == kRankPadGemm, "the per-tile extension table is built for this tile");
@@ -480,8 +479,16 @@ static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, const 
         if (e != hipSuccess) return e;
         attr_done = true;
     }
+    // persistent grid: one workgroup per compute unit (256 on an MI355X; a workgroup takes a whole CU's LDS)
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
+            return hipErrorInvalidDevice;
+        n_cu = v;
+    }
     const int n_tiles = tiles_m * tiles_n;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < kGemmGrid ? n_tiles : kGemmGrid)), dim3(512), kGemmLds, st, mv,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < n_cu ? n_tiles : n_cu)), dim3(512), kGemmLds, st, mv,
                        static_cast<const uint16_t *>(S), static_cast<const uint16_t *>(W),
                        static_cast<const uint16_t *>(side), static_cast<const uint16_t *>(ap),
                        static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n, (int)h.T, (int)h.D,
