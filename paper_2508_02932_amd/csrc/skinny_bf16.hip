@@ -4,7 +4,8 @@
 // Both stream one big [T][C] matrix once (C = d_in or d_out) against a small per-adapter matrix
 // whose rows are output columns with the contraction index contiguous (A_k^T packed, or B_k as it
 // is).  They are bound by HBM, so the kernel is built around keeping bytes in flight: operands go
-// HBM -> LDS directly (global_load_lds) through a three-stage ring, the contraction is split over
+// HBM -> LDS directly (global_load_lds) through a two-stage ring (more workgroups per compute unit
+// pay more here than a deeper ring: measured), the contraction is split over
 // workgroups when the batch has too few token blocks to fill the chip, and the arithmetic runs on
 // 16x16x32 bf16 MFMA with fp32 accumulators so that ranks up to 128 stay far below the
 // matrix-core roof.  The rank is never tiled (appendix C.2: tile the sequence and hidden
@@ -27,10 +28,12 @@ __device__ inline uint16_t bf16_rne(float f)
 }
 
 constexpr int SK_BK = 64;                              // contraction elements per stage
-constexpr int SK_NST = 3;                              // ring stages
+constexpr int SK_NST = 2;                              // ring stages: 32-64 KB of LDS per workgroup, so 2-3 fit on a compute unit
 constexpr int SK_XT = kSkinnyRows * SK_BK * 2;         // 16 KB: [128 tokens][64 k]
-constexpr int SK_XL = kSkinnyRows / 8 / 4;             // token-tile load instructions per wave per stage
-constexpr int SK_MB = kSkinnyRows / 16 / 4;            // 16-token MFMA blocks per wave
+constexpr int SK_NW = kSkinnyRows / 32;                // waves per workgroup: a wave owns 32 tokens
+constexpr int SK_XL = kSkinnyRows / 8 / SK_NW;         // token-tile load instructions per wave per stage (4)
+constexpr int SK_MB = kSkinnyRows / 16 / SK_NW;        // 16-token MFMA blocks per wave (2)
+constexpr int SK_BL = (PLORA_MAX_RANK / 8 + SK_NW - 1) / SK_NW;   // small-matrix load instructions per wave per stage, at most
 constexpr int SK_MAXNB = PLORA_MAX_RANK / 16;
 
 // s_waitcnt vmcnt(n) for a wave-uniform runtime n (the instruction takes an immediate)
@@ -51,7 +54,7 @@ __device__ inline void wait_vmcnt_dyn(int n)
 // conflict free).  Wave w owns tokens 32w..32w+31 and every rank block, so nothing is reduced
 // across waves.  Output: the fp32 partial tile [128][r16] of this slice.
 //   mode 0: small matrix = packed A_k^T [r16][C] (rows >= r are zero),  mode 1: B_k [r][C].
-__global__ void __launch_bounds__(256) k_skinny(MetaView mv, int mode, const uint16_t *__restrict__ S, int C,
+__global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, const uint16_t *__restrict__ S, int C,
                                                const uint16_t *__restrict__ at, const uint16_t *__restrict__ zero,
                                                float *__restrict__ part, int stages_per_split)
 {
@@ -87,19 +90,19 @@ __global__ void __launch_bounds__(256) k_skinny(MetaView mv, int mode, const uin
     int xchunk[SK_XL];
 #pragma unroll
     for (int jj = 0; jj < SK_XL; ++jj) {
-        const int u = (wave + 4 * jj) * 8 + lrow;
+        const int u = (wave + SK_NW * jj) * 8 + lrow;
         xchunk[jj] = (lane & 7) ^ ((u >> 1) & 7);
         xok[jj] = u < nt;
         xp[jj] = S + (int64_t)(g.row0 + t0 + (xok[jj] ? u : 0)) * C + (int64_t)st0 * SK_BK + xchunk[jj] * 8;
     }
     const int nbi = g.r16 / 8;                                    // small-matrix load instructions per stage
-    const int my_b = (nbi > wave) ? (nbi - wave + 3) / 4 : 0;     // ... of which this wave issues my_b
-    const uint16_t *bp[4];
-    bool bok[4];
-    int bchunk[4];
+    const int my_b = (nbi > wave) ? (nbi - wave + SK_NW - 1) / SK_NW : 0;     // ... of which this wave issues my_b
+    const uint16_t *bp[SK_BL];
+    bool bok[SK_BL];
+    int bchunk[SK_BL];
 #pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-        const int u = (wave + 4 * jj) * 8 + lrow;
+    for (int jj = 0; jj < SK_BL; ++jj) {
+        const int u = (wave + SK_NW * jj) * 8 + lrow;
         bchunk[jj] = (lane & 7) ^ ((u >> 1) & 7);
         bok[jj] = u < brows;
         bp[jj] = Bm + (int64_t)(bok[jj] ? u : 0) * C + (int64_t)st0 * SK_BK + bchunk[jj] * 8;
@@ -115,13 +118,13 @@ __global__ void __launch_bounds__(256) k_skinny(MetaView mv, int mode, const uin
 #pragma unroll
         for (int jj = 0; jj < SK_XL; ++jj) {
             const bool ok = xok[jj] && (k0 + xchunk[jj] * 8 < C);
-            load16(ok ? xp[jj] + (int64_t)st * SK_BK : zero, base + (wave + 4 * jj) * 1024);
+            load16(ok ? xp[jj] + (int64_t)st * SK_BK : zero, base + (wave + SK_NW * jj) * 1024);
         }
 #pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
+        for (int jj = 0; jj < SK_BL; ++jj) {
             if (jj < my_b) {
                 const bool ok = bok[jj] && (k0 + bchunk[jj] * 8 < C);
-                load16(ok ? bp[jj] + (int64_t)st * SK_BK : zero, base + SK_XT + (wave + 4 * jj) * 1024);
+                load16(ok ? bp[jj] + (int64_t)st * SK_BK : zero, base + SK_XT + (wave + SK_NW * jj) * 1024);
             }
         }
     };
@@ -267,7 +270,7 @@ hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode,
         if (e != hipSuccess) return e;
         lds_allowed = lds;
     }
-    hipLaunchKernelGGL(k_skinny, dim3((unsigned)h.n_blocks, (unsigned)n_split), dim3(256), lds, st, mv, mode,
+    hipLaunchKernelGGL(k_skinny, dim3((unsigned)h.n_blocks, (unsigned)n_split), dim3(64 * SK_NW), lds, st, mv, mode,
                        static_cast<const uint16_t *>(S), (int)C, static_cast<const uint16_t *>(at),
                        static_cast<const uint16_t *>(zero), part, per);
     hipError_t e = hipGetLastError();
