@@ -33,8 +33,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default: the headline one)")
     ap.add_argument("--linear", type=int, default=0, help="which linear of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--no-sequential", action="store_true",
-                    help="skip the context leg that runs the same step one adapter per call")
+    ap.add_argument("--sequential", action="store_true",
+                    help="also time the same step issued one adapter per call (context figure; off by default so "
+                         "that a profile of the default command only holds the packed kernels)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling this script)")
@@ -112,7 +113,7 @@ def main():
     # backward call per adapter on its own rows with a single-segment description - the launch pattern
     # that packing replaces (the paper's kernel tables compare against it)
     sequential = None
-    if not args.no_sequential and lay.n_adapters > 0 and all(int(a) >= 0 for a in lay.seg_adapter) \
+    if args.sequential and lay.n_adapters > 0 and all(int(a) >= 0 for a in lay.seg_adapter) \
             and len(set(int(a) for a in lay.seg_adapter)) == lay.n_seg:
         subs = []
         h_off = 0
