@@ -203,3 +203,36 @@ def test_run_twice_bitwise_identical():
         outs.append([gh.to_np(dp.y), gh.to_np(dp.dx)] + [gh.to_np(a) for a in dp.dA] + [gh.to_np(b) for b in dp.dB])
     for a, b in zip(*outs):
         assert np.array_equal(a, b)
+
+
+def test_side_stream_and_workspace_reuse():
+    """The calls enqueue on the stream they are given (here a second stream of default priority, with the
+    inputs produced on it) and leave nothing behind in the workspace that a later call with another
+    description depends on: two different problems alternate on one workspace and one stream and each
+    keeps giving its own bits."""
+    import torch
+    import gpu_harness as gh
+    from paper_2508_02932_amd import plora
+    lin_a = wl.small("stream_a", "bf16", 320, 264, lengths=[150, 0, 221], seg_adapter=[1, 0, 0], ranks=[40, 8],
+                     scales=[1.0, 2.0], seed=97)
+    lin_b = wl.small("stream_b", "bf16", 264, 320, lengths=[97, 130], seg_adapter=[0, -1], ranks=[128],
+                     scales=[0.5], seed=101)
+    ref = {}
+    for lin in (lin_a, lin_b):                                   # reference bits on the default stream
+        dp, _ = run_and_compare(lin)
+        ref[lin.name] = [gh.to_np(dp.y), gh.to_np(dp.dx)] + [gh.to_np(a) for a in dp.dA] + [gh.to_np(b) for b in dp.dB]
+    side = torch.cuda.Stream()
+    dps = {lin.name: gh.upload(lin, lin.tensors()) for lin in (lin_a, lin_b)}
+    ws = torch.empty(max(d.ws.numel() for d in dps.values()), dtype=torch.uint8, device="cuda")
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        for rep in range(3):
+            for name, dp in dps.items():
+                say(f"[case] side stream, rep {rep}, {name}")
+                plora.plora_linear_fwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.y, dp.h, ws, stream=side)
+                plora.plora_linear_bwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.dy, dp.h, dp.dx, dp.dA, dp.dB, ws, stream=side)
+    side.synchronize()
+    for name, dp in dps.items():
+        got = [gh.to_np(dp.y), gh.to_np(dp.dx)] + [gh.to_np(a) for a in dp.dA] + [gh.to_np(b) for b in dp.dB]
+        for a, b in zip(got, ref[name]):
+            assert np.array_equal(a, b), name
