@@ -73,3 +73,15 @@ class Problem:
         parts = [np.arange(self.seg_off[s], self.seg_off[s + 1], dtype=np.int64)
                  for s in range(self.n_seg) if self.seg_adapter[s] == k]
         return np.concatenate(parts) if parts else np.zeros(0, dtype=np.int64)
+
+    def take_rows(self, rows) -> "Problem":
+        """The same layer on a subset of the tokens: rows (sorted, unique) keep their segment,
+        hence their adapter; segments that lose all their rows become empty.  Pure indexing -
+        every token's outputs depend on its own row and its adapter only (section 2.4), so
+        y, h, dx, g of the sub-problem are those rows of the full problem."""
+        rows = np.asarray(rows, dtype=np.int64)
+        assert rows.ndim == 1 and (len(rows) == 0 or (np.all(np.diff(rows) > 0) and rows[0] >= 0
+                                                      and rows[-1] < self.T))
+        off = np.searchsorted(rows, self.seg_off.astype(np.int64), side="left").astype(np.int32)
+        return Problem(self.x[rows], self.W, self.A, self.B, off, self.seg_adapter, self.scale,
+                       self.rank)

@@ -397,3 +397,107 @@ def test_loops_rejects_bad_tables():
     assert oracle.loops.check(oracle.Problem(seg_off=[0, 3, 2, 4], seg_adapter=[0, 0, 0], **base)) != 0
     assert oracle.loops.check(oracle.Problem(seg_off=[0, 4], seg_adapter=[1], **base)) != 0
     assert oracle.loops.check(oracle.Problem(seg_off=[0, 4], seg_adapter=[-2], **base)) != 0
+
+
+# ---------------------------------------------------------------------------------------------
+# the partial entry points used at full size (matmul writing): the activation alone, the weight
+# gradients alone, and a subset of the token rows.  Each is pinned by something other than the
+# function it abbreviates: pure-Python brute force, finite differences, the hand-worked example,
+# and the scalar-loop oracle (itself pinned above).
+# ---------------------------------------------------------------------------------------------
+def test_low_rank_partials_hand_worked_and_brute_force():
+    with open(os.path.join(GOLDEN, "hand_worked_rank1.json")) as f:
+        gold = json.load(f)
+    p = oracle.Problem(gold["x"], gold["W"], [np.array(a) for a in gold["A"]],
+                       [np.array(b) for b in gold["B"]], gold["seg_off"], gold["seg_adapter"],
+                       gold["scale"])
+    dy = np.array(gold["dy"], dtype=np.float32)
+    h = oracle.matmul.low_rank_activation(p)
+    dA, dB = oracle.matmul.low_rank_gradients(p, dy)
+    e = gold["expect"]
+    assert np.array_equal(h[0, :1], np.array(e["h_row0"], dtype=np.float64))
+    assert np.array_equal(h[1], np.zeros_like(h[1]))
+    assert np.array_equal(dA[0], np.array(e["dA"][0], dtype=np.float64))
+    assert np.array_equal(dB[0], np.array(e["dB"][0], dtype=np.float64))
+    # brute force (math.fsum over the definition) on a ragged tiny case
+    lin = wl.small("tiny2", "f32", 7, 6, lengths=[3, 0, 2, 4], seg_adapter=[1, 0, -1, 1], ranks=[2, 3],
+                   scales=[1.5, -0.5], seed=19)
+    t = lin.tensors()
+    p = make_problem(oracle, lin, t)
+    h = oracle.matmul.low_rank_activation(p)
+    dA, dB = oracle.matmul.low_rank_gradients(p, t.dy)
+    X, DY = t.x.astype(float), t.dy.astype(float)
+    seg_of = []
+    for s in range(p.n_seg):
+        seg_of += [int(p.seg_adapter[s])] * int(p.seg_off[s + 1] - p.seg_off[s])
+    for tt in range(p.T):
+        k = seg_of[tt]
+        want = np.zeros(h.shape[1])
+        if k >= 0:
+            A = t.A[k].astype(float)
+            want[:A.shape[1]] = [math.fsum(X[tt, i] * A[i, j] for i in range(p.D)) for j in range(A.shape[1])]
+        assert np.allclose(h[tt], want, rtol=0, atol=1e-14)
+    for k in range(p.n_adapters):
+        r, sc = int(p.rank[k]), float(p.scale[k])
+        A, B = t.A[k].astype(float), t.B[k].astype(float)
+        toks = [tt for tt in range(p.T) if seg_of[tt] == k]
+        for i, j in itertools.product(range(p.D), range(r)):
+            want = math.fsum(X[tt, i] * sc * math.fsum(DY[tt, n] * B[j, n] for n in range(p.K)) for tt in toks)
+            assert abs(dA[k][i, j] - want) < 1e-12
+        for j, n in itertools.product(range(r), range(p.K)):
+            want = sc * math.fsum(math.fsum(X[tt, i] * A[i, j] for i in range(p.D)) * DY[tt, n] for tt in toks)
+            assert abs(dB[k][j, n] - want) < 1e-12
+
+
+def test_low_rank_gradients_finite_differences():
+    lin, t, p = ragged_case(seed=17, D=12, K=10)
+    dy64 = t.dy.astype(np.float64)
+    dA, dB = oracle.matmul.low_rank_gradients(p, t.dy)
+    eps = 2.0 ** -6
+
+    def loss(A, B):           # through the scalar-loop forward: a different writing of the layer
+        y, _ = oracle.loops.forward(oracle.Problem(t.x, t.W, A, B, p.seg_off, p.seg_adapter, p.scale))
+        return float(np.sum(y * dy64))
+
+    rng = np.random.default_rng(1)
+    for k in range(p.n_adapters):
+        r = int(p.rank[k])
+        for _ in range(10):
+            i, j, n = int(rng.integers(p.D)), int(rng.integers(r)), int(rng.integers(p.K))
+            Ap = [a.copy() for a in t.A]
+            Am = [a.copy() for a in t.A]
+            Ap[k][i, j] += eps
+            Am[k][i, j] -= eps
+            fd = (loss(Ap, t.B) - loss(Am, t.B)) / (float(Ap[k][i, j]) - float(Am[k][i, j]))
+            assert abs(fd - dA[k][i, j]) < 1e-9
+            Bp = [b.copy() for b in t.B]
+            Bm = [b.copy() for b in t.B]
+            Bp[k][j, n] += eps
+            Bm[k][j, n] -= eps
+            fd = (loss(t.A, Bp) - loss(t.A, Bm)) / (float(Bp[k][j, n]) - float(Bm[k][j, n]))
+            assert abs(fd - dB[k][j, n]) < 1e-9
+
+
+def test_partials_and_row_subsets_equal_scalar_loops():
+    lin = wl.small("mid2", "bf16", 136, 120, lengths=[70, 0, 33, 130, 1, 64],
+                   seg_adapter=[2, 1, 0, 1, -1, 2], ranks=[8, 24, 64], scales=[2.0, 2.0, 0.5], seed=37)
+    t = lin.tensors()
+    p = make_problem(oracle, lin, t)
+    y1, h1 = oracle.loops.forward(p)
+    dx1, g1, dA1, dB1 = oracle.loops.backward(p, t.dy)
+    assert scaled_err(oracle.matmul.low_rank_activation(p), h1) < 1e-13
+    dA2, dB2 = oracle.matmul.low_rank_gradients(p, t.dy)
+    for k in range(p.n_adapters):
+        assert scaled_err(dA2[k], dA1[k]) < 1e-12 and scaled_err(dB2[k], dB1[k]) < 1e-12
+    # a subset of rows through take_rows: rows next to every segment boundary, a run, the ends
+    rows = np.array([0, 1, 69, 70, 71, 102, 103, 104, 150, 151, 152, 153, 232, 233, 234, 297])
+    sub = p.take_rows(rows)
+    assert sub.T == len(rows) and sub.n_seg == p.n_seg
+    for impl in IMPLS:
+        ys, hs = impl.forward(sub)
+        dxs, gs, _, _ = impl.backward(sub, t.dy[rows])
+        assert scaled_err(ys, y1[rows]) < 1e-13 and scaled_err(hs, h1[rows]) < 1e-13
+        assert scaled_err(dxs, dx1[rows]) < 1e-13 and scaled_err(gs, g1[rows]) < 1e-13
+    ys, _ = oracle.loops.forward(sub)
+    assert np.array_equal(ys, oracle.loops.fwd_rows(p, rows)[0])      # the C loops: bit for bit
+    assert p.take_rows(np.zeros(0, dtype=np.int64)).T == 0
