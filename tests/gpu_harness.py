@@ -1,7 +1,9 @@
 """Runs the HIP library on a workload and brings the results back as numpy arrays.
 
 Only marshalling: torch owns the device memory, every step of the layer runs in libplora.
-Outputs are pre-filled with NaN so that an element the kernels fail to write shows up.
+Outputs are pre-filled with NaN so that an element the kernels fail to write shows up, and every
+output and the workspace sit between two 4 KB guard bands of a byte pattern that ``check_guards``
+expects to find untouched (a write before the start or past the end of a buffer lands there).
 """
 from __future__ import annotations
 
@@ -30,6 +32,32 @@ def to_np(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy()
 
 
+GUARD_BYTES = 4096
+GUARD_BYTE = 0xC5
+
+
+def guarded(shape, dtype: torch.dtype, fill, guards: list, name: str) -> torch.Tensor:
+    """A tensor of the given shape whose storage lies between two guard bands; registers the bands."""
+    numel = int(np.prod(shape)) if len(shape) else 1
+    nbytes = numel * torch.empty(0, dtype=dtype).element_size()
+    pad = (-nbytes) % 256
+    base = torch.full((GUARD_BYTES + nbytes + pad + GUARD_BYTES,), GUARD_BYTE, dtype=torch.uint8, device="cuda")
+    view = base[GUARD_BYTES:GUARD_BYTES + nbytes].view(dtype).view(*shape)
+    if fill is not None:
+        view.fill_(fill)
+    guards.append((name, base, nbytes))
+    return view
+
+
+def check_guards(p: "DeviceProblem") -> None:
+    """Raises if any byte of a guard band changed (call after synchronising)."""
+    for name, base, nbytes in p.guards:
+        lo = base[:GUARD_BYTES]
+        hi = base[GUARD_BYTES + nbytes:]
+        assert bool((lo == GUARD_BYTE).all()), f"write before the start of {name}"
+        assert bool((hi == GUARD_BYTE).all()), f"write past the end of {name}"
+
+
 @dataclass
 class DeviceProblem:
     lin: wl.Linear
@@ -45,6 +73,7 @@ class DeviceProblem:
     dx: torch.Tensor
     dA: List[torch.Tensor]
     dB: List[torch.Tensor]
+    guards: list
 
 
 def upload(lin: wl.Linear, t: wl.Tensors) -> DeviceProblem:
@@ -52,19 +81,20 @@ def upload(lin: wl.Linear, t: wl.Tensors) -> DeviceProblem:
     tdt = torch.bfloat16 if lin.dtype == "bf16" else torch.float32
     ws_bytes = plora.plora_workspace_bytes(d)
     assert ws_bytes > 0
-    dev = "cuda"
     nan = float("nan")
     T, D, K = lin.layout.T, lin.D, lin.K
+    g: list = []
     return DeviceProblem(
         lin, d, to_dev(t.x, lin.dtype), to_dev(t.W, lin.dtype),
         [to_dev(a, lin.dtype) for a in t.A], [to_dev(b, lin.dtype) for b in t.B],
         None if t.dy is None else to_dev(t.dy, lin.dtype),
-        torch.empty(ws_bytes, dtype=torch.uint8, device=dev),
-        torch.full((max(plora.plora_h_elems(d), 1),), nan, dtype=torch.float32, device=dev),
-        torch.full((T, K), nan, dtype=tdt, device=dev),
-        torch.full((T, D), nan, dtype=tdt, device=dev),
-        [torch.full((D, int(r)), nan, dtype=torch.float32, device=dev) for r in lin.layout.rank],
-        [torch.full((int(r), K), nan, dtype=torch.float32, device=dev) for r in lin.layout.rank])
+        guarded((ws_bytes,), torch.uint8, None, g, "workspace"),
+        guarded((max(plora.plora_h_elems(d), 1),), torch.float32, nan, g, "h_saved"),
+        guarded((T, K), tdt, nan, g, "y"),
+        guarded((T, D), tdt, nan, g, "dx"),
+        [guarded((D, int(r)), torch.float32, nan, g, f"dA[{k}]") for k, r in enumerate(lin.layout.rank)],
+        [guarded((int(r), K), torch.float32, nan, g, f"dB[{k}]") for k, r in enumerate(lin.layout.rank)],
+        g)
 
 
 def forward(p: DeviceProblem, save_h: bool = True):

@@ -42,6 +42,7 @@ def run_and_compare(lin, t=None, impl=None, save_h=True, check_h=True):
     say("  backward")
     gh.backward(dp, use_saved_h=save_h)
     torch.cuda.synchronize()
+    gh.check_guards(dp)
     y = gh.to_np(dp.y)
     dx = gh.to_np(dp.dx)
     errs = {"y": scaled_err(y, y_o), "dx": scaled_err(dx, dx_o)}
@@ -125,6 +126,7 @@ def test_edge_cases(dtype):
     gh.forward(dp)
     gh.backward(dp)
     torch.cuda.synchronize()
+    gh.check_guards(dp)
     assert not gh.to_np(dp.dA[0]).any() and not gh.to_np(dp.dB[0]).any()
 
 
@@ -142,6 +144,7 @@ def test_skip_outputs():
     gh.forward(dp)
     gh.backward(dp, want_dx=False)
     torch.cuda.synchronize()
+    gh.check_guards(dp)
     assert np.isnan(gh.to_np(dp.dx)).all()
     assert scaled_err(gh.to_np(dp.dA[1]), dA_o[1]) < 2e-2
     dp = gh.upload(lin, t)
@@ -149,6 +152,7 @@ def test_skip_outputs():
     gh.forward(dp)
     gh.backward(dp, want_w=False)
     torch.cuda.synchronize()
+    gh.check_guards(dp)
     assert np.isnan(gh.to_np(dp.dA[0])).all() and np.isnan(gh.to_np(dp.dB[1])).all()
     assert scaled_err(gh.to_np(dp.dx), dx_o) < 2e-2
 
@@ -179,6 +183,7 @@ def test_bf16_exact_integers():
     gh.forward(dp)
     gh.backward(dp)
     torch.cuda.synchronize()
+    gh.check_guards(dp)
     assert np.array_equal(gh.to_np(dp.y), wl.round_to_bf16(y_o.astype(np.float32)))
     assert np.array_equal(gh.to_np(dp.dx), wl.round_to_bf16(dx_o.astype(np.float32)))
     for k in range(2):
@@ -233,6 +238,7 @@ def test_side_stream_and_workspace_reuse():
                 plora.plora_linear_bwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.dy, dp.h, dp.dx, dp.dA, dp.dB, ws, stream=side)
     side.synchronize()
     for name, dp in dps.items():
+        gh.check_guards(dp)
         got = [gh.to_np(dp.y), gh.to_np(dp.dx)] + [gh.to_np(a) for a in dp.dA] + [gh.to_np(b) for b in dp.dB]
         for a, b in zip(got, ref[name]):
             assert np.array_equal(a, b), name

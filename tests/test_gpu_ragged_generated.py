@@ -1,0 +1,67 @@
+"""Generated small ragged cases on the GPU (hypothesis, derandomised so that every run draws the
+same cases): random segment counts and lengths (empty ones included), repeated and base-only
+adapters, adapters without tokens, ranks anywhere in 1..128, hidden sizes that are multiples of 8
+but of no tile.  Each case is compared element by element with the scalar-loop oracle.  No
+shrinking and no second example after a failure: the run stops at the first failing case."""
+import sys
+
+import numpy as np
+import pytest
+from hypothesis import HealthCheck, Phase, given, settings, strategies as st
+
+import oracle
+from paper_2508_02932_amd import workloads as wl
+from util import make_problem, scaled_err
+
+pytestmark = pytest.mark.gpu
+TOL = {"bf16": 2e-2, "f32": 1e-5}
+
+
+@st.composite
+def ragged_linear(draw):
+    dtype = draw(st.sampled_from(["bf16", "bf16", "bf16", "f32"]))
+    big = dtype == "bf16"
+    D = 8 * draw(st.integers(1, 72 if big else 12))
+    K = 8 * draw(st.integers(1, 72 if big else 12))
+    n_ad = draw(st.integers(1, 5))
+    ranks = [draw(st.sampled_from([1, 2, 7, 8, 16, 24, 33, 64, 100, 128])) for _ in range(n_ad)]
+    scales = [draw(st.sampled_from([0.25, 0.5, 1.0, 2.0, 4.0])) for _ in range(n_ad)]
+    n_seg = draw(st.integers(1, 7))
+    max_len = 330 if big else 70
+    lengths = [draw(st.one_of(st.just(0), st.integers(1, max_len))) for _ in range(n_seg)]
+    seg_adapter = [draw(st.integers(-1, n_ad - 1)) for _ in range(n_seg)]
+    seed = draw(st.integers(0, 999))
+    return wl.small(f"gen_{dtype}_{seed}", dtype, D, K, lengths, seg_adapter, ranks, scales, seed=seed)
+
+
+@settings(max_examples=24, deadline=None, derandomize=True, database=None, phases=[Phase.generate],
+          report_multiple_bugs=False, suppress_health_check=list(HealthCheck))
+@given(lin=ragged_linear(), save_h=st.booleans())
+def test_generated_ragged_cases(lin, save_h):
+    import torch
+    import gpu_harness as gh
+    lay = lin.layout
+    print(f"[case] {lin.name} T={lay.T} D={lin.D} K={lin.K} ranks={lay.rank.tolist()} "
+          f"segs={np.diff(lay.seg_off).tolist()} adapters={lay.seg_adapter.tolist()} save_h={save_h}", flush=True)
+    sys.stdout.flush()
+    t = lin.tensors()
+    p = make_problem(oracle, lin, t)
+    y_o, h_o = oracle.loops.forward(p)
+    dx_o, _, dA_o, dB_o = oracle.loops.backward(p, t.dy)
+    dp = gh.upload(lin, t)
+    gh.forward(dp, save_h=save_h)
+    gh.backward(dp, use_saved_h=save_h)
+    torch.cuda.synchronize()
+    gh.check_guards(dp)
+    tol = TOL[lin.dtype]
+    errs = {}
+    if lay.T:
+        errs["y"] = scaled_err(gh.to_np(dp.y), y_o)
+        errs["dx"] = scaled_err(gh.to_np(dp.dx), dx_o)
+    if save_h and lay.sum_Lr() > 0:
+        errs["h"] = scaled_err(gh.ragged_h_to_rows(lin, gh.to_np(dp.h)[:lay.sum_Lr()]), h_o)
+    for k in range(lay.n_adapters):
+        errs[f"dA{k}"] = scaled_err(gh.to_np(dp.dA[k]), dA_o[k])
+        errs[f"dB{k}"] = scaled_err(gh.to_np(dp.dB[k]), dB_o[k])
+    for k, v in errs.items():
+        assert np.isfinite(v) and v <= tol, (lin.name, k, v, tol)
