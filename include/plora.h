@@ -121,6 +121,23 @@ plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void 
                               float *h_saved, void *workspace, size_t ws_bytes, void *hip_stream);
 
 /*
+ * Forward for callers that cannot allocate device memory and have no workspace to hand over:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, results and error codes as plora_linear_fwd, without the workspace: the temporary
+ * storage is a scratch array of PLORA_NOALLOC_SCRATCH_BYTES that is part of the library's device
+ * image (one copy per GPU, held until the process ends).  The call allocates and frees nothing.
+ * A description whose plora_workspace_bytes exceeds the scratch size is refused with
+ * PLORA_ERR_WORKSPACE before anything is enqueued.  Every call on one GPU uses that GPU's one
+ * array (it keeps the previous call's contents; the call rewrites what it reads), so calls of
+ * this entry point that overlap on one GPU - different streams, or different host threads - race;
+ * order them on one stream.
+ */
+#define PLORA_NOALLOC_SCRATCH_BYTES (64u << 20)
+plora_status plora_linear_fwd_noalloc(const plora_desc *desc, const void *x, const void *W,
+                                      const void *const *A, const void *const *B, void *y,
+                                      float *h_saved, void *hip_stream);
+
+/*
  * Backward (appendix C.2, cases 1-4; no gradient for W).
  *   x, W, A, B as in the forward call;  dy DEVICE [T][d_out]
  *   h_saved  DEVICE fp32 activation written by the forward call with the same inputs, or NULL

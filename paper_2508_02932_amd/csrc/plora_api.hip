@@ -5,6 +5,7 @@
 
 #include <cstring>
 #include <algorithm>
+#include <mutex>
 #include <vector>
 
 namespace plora {
@@ -348,6 +349,41 @@ int plora_kernel_time(int cls, float *total_ms, int *count)
     }
     *total_ms = tot; *count = n;
     return 0;
+}
+
+// Scratch memory of plora_linear_fwd_noalloc: one array per GPU, resident from the first use of the
+// library on that GPU until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the device address looked up once per device.
+__device__ __align__(256) unsigned char g_noalloc_scratch[PLORA_NOALLOC_SCRATCH_BYTES];
+
+static plora_status noalloc_scratch(void **out)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void *ptr[kMaxDevices] = {};
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PLORA_ERR_HIP;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(g_noalloc_scratch)) != hipSuccess || !p) return PLORA_ERR_HIP;
+        ptr[dev] = p;
+    }
+    *out = ptr[dev];
+    return PLORA_OK;
+}
+
+plora_status plora_linear_fwd_noalloc(const plora_desc *desc, const void *x, const void *W,
+                                      const void *const *A, const void *const *B, void *y, float *h_saved,
+                                      void *hip_stream)
+{
+    const size_t need = plora_workspace_bytes(desc);
+    if (need == 0) return validate(desc) == PLORA_OK ? PLORA_ERR_WORKSPACE : validate(desc);
+    if (need > (size_t)PLORA_NOALLOC_SCRATCH_BYTES) return PLORA_ERR_WORKSPACE;
+    void *scratch = nullptr;
+    plora_status ps = noalloc_scratch(&scratch);
+    if (ps != PLORA_OK) return ps;
+    return plora_linear_fwd(desc, x, W, A, B, y, h_saved, scratch, PLORA_NOALLOC_SCRATCH_BYTES, hip_stream);
 }
 
 plora_status plora_linear_fwd(const plora_desc *desc, const void *x, const void *W,

@@ -23,7 +23,7 @@ PLORA_MAX_RANK, PLORA_MAX_ADAPTERS, PLORA_MAX_SEGMENTS = 128, 256, 1024
 KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "pack": 6, "convert": 7}
 
 EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_workspace_bytes",
-           "plora_build_metadata", "plora_linear_fwd", "plora_linear_bwd",
+           "plora_build_metadata", "plora_linear_fwd", "plora_linear_fwd_noalloc", "plora_linear_bwd",
            "plora_set_kernel_timing", "plora_kernel_time"]
 
 
@@ -62,6 +62,8 @@ def lib():
         L.plora_build_metadata.argtypes = [C.POINTER(plora_desc), C.c_int32, C.c_void_p, C.c_void_p, C.c_int64]
         L.plora_linear_fwd.restype = C.c_int
         L.plora_linear_fwd.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
+        L.plora_linear_fwd_noalloc.restype = C.c_int
+        L.plora_linear_fwd_noalloc.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 7
         L.plora_linear_bwd.restype = C.c_int
         L.plora_linear_bwd.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
         L.plora_set_kernel_timing.restype = None
@@ -157,6 +159,17 @@ def plora_linear_fwd(d: Desc, x, W, A: Sequence, B: Sequence, y, h_saved, worksp
     code = lib().plora_linear_fwd(d.ref, _ptr(x), _ptr(W), pa, pb, _ptr(y), _ptr(h_saved),
                                   _ptr(workspace), workspace.numel() * workspace.element_size(),
                                   _stream(stream))
+    _check(code)
+
+
+NOALLOC_SCRATCH_BYTES = 64 << 20
+
+
+def plora_linear_fwd_noalloc(d: Desc, x, W, A: Sequence, B: Sequence, y, h_saved, stream=None) -> None:
+    """Forward on the library's own per-GPU scratch array (no workspace argument, nothing allocated)."""
+    ka, pa = _ptr_table(A)
+    kb, pb = _ptr_table(B)
+    code = lib().plora_linear_fwd_noalloc(d.ref, _ptr(x), _ptr(W), pa, pb, _ptr(y), _ptr(h_saved), _stream(stream))
     _check(code)
 
 
