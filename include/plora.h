@@ -26,7 +26,12 @@
  *     the default stream) and never synchronise.  Two calls that share a workspace must be
  *     ordered on one stream.
  *   - Every argument is validated before anything is enqueued; on error nothing is launched and
- *     no output is touched.  No exception or abort crosses this boundary.
+ *     no output is touched.  No exception or abort crosses this boundary (a failed host
+ *     allocation comes back as PLORA_ERR_INTERNAL).
+ *   - Thread safety: calls may come from several host threads and on several devices (the current
+ *     HIP device of the calling thread is used); the only state the library keeps is a small
+ *     cache of derived metadata keyed by the description and per-device launch set-up, both behind
+ *     locks.  Calls that share a workspace must be ordered on one stream.
  *   - x, W, A_k, B_k, y, dy, dx have the element type desc->dtype.  The saved low-rank
  *     activation h and the gradients dA_k, dB_k are always fp32.  bf16 results are rounded to
  *     nearest-even from fp32 accumulators.
@@ -48,14 +53,17 @@ extern "C" {
 typedef enum {
     PLORA_OK = 0,
     PLORA_ERR_NULL = 1,         /* a required pointer is NULL                                   */
-    PLORA_ERR_SHAPE = 2,        /* T, d_in or d_out negative / zero / not a multiple of 8 (bf16)*/
+    PLORA_ERR_SHAPE = 2,        /* T, d_in or d_out negative / zero / not a multiple of 8 (bf16),
+                                   d_in or d_out above 2^22, T above 2^31 - 1, more than 2^30
+                                   256 x 256 output tiles, fp32 with T above 65535 * 64          */
     PLORA_ERR_SEGMENTS = 3,     /* offsets do not start at 0, end at T, or decrease             */
     PLORA_ERR_ADAPTER = 4,      /* adapter id outside [-1, n_adapters) or too many of them      */
     PLORA_ERR_RANK = 5,         /* rank outside [1, PLORA_MAX_RANK]                             */
     PLORA_ERR_ALIGN = 6,        /* a device pointer is not 16-byte aligned                      */
     PLORA_ERR_WORKSPACE = 7,    /* workspace NULL or smaller than plora_workspace_bytes()       */
     PLORA_ERR_UNSUPPORTED = 8,  /* unknown dtype                                                */
-    PLORA_ERR_HIP = 9           /* a HIP call failed (launch error)                             */
+    PLORA_ERR_HIP = 9,          /* a HIP call failed (launch error)                             */
+    PLORA_ERR_INTERNAL = 10     /* host memory allocation failed or another internal error      */
 } plora_status;
 
 typedef enum { PLORA_BF16 = 0, PLORA_F32 = 1 } plora_dtype;
@@ -93,8 +101,9 @@ size_t plora_h_elems(const plora_desc *desc);
 size_t plora_workspace_bytes(const plora_desc *desc);
 
 /*
- * Segment-packing metadata, computed on the host exactly as the launches use it (exposed so
- * that it can be checked against brute force without a GPU).
+ * Layout of the saved activation and a token-block view of the packing (host only; what a caller
+ * needs to address h_saved, and a simple form of the segment table for tests).  The tables the
+ * kernels themselves read are exported by plora_debug_metadata (plora_debug.h).
  *   h_off_out   [n_seg+1] element offset of each segment inside the saved activation
  *               (int64 prefix sums of length x rank); may be NULL.
  *   blocks_out  token blocks of at most block_rows rows that never straddle a segment, in row
@@ -152,18 +161,6 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
                               const float *h_saved, void *dx, float *const *dA,
                               float *const *dB, void *workspace, size_t ws_bytes,
                               void *hip_stream);
-
-/*
- * Timing hook for benchmarks.  While enabled (non-zero), every kernel class of every fwd / bwd call
- * is bracketed by a pair of HIP events recorded on the call's own stream.  Enabling clears earlier
- * records; at most 16384 brackets are kept.  plora_kernel_time sums the recorded durations of
- * one class (milliseconds) and counts them; the caller must have synchronised the streams first.
- * Classes: 0 base GEMM forward (with the fused expand), 1 dX GEMM (with the fused low-rank
- * term), 2 shrink, 3 dH, 4 dB, 5 dA, 6 packing of A_k, 7 conversion of a saved activation into
- * the transposed bf16 operand of dB.  Returns 0, or -1 on a bad argument or event error.  Not thread-safe.
- */
-void plora_set_kernel_timing(int enabled);
-int plora_kernel_time(int kernel_class, float *total_ms, int *count);
 
 #ifdef __cplusplus
 }

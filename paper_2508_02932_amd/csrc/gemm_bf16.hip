@@ -8,7 +8,9 @@
 // kernel beforehand; here it only lengthens the K loop of the tiles whose rows belong to adapter k,
 // so the base output never makes an extra trip through HBM.  Row tiles are uniform over the whole
 // batch; a tile that straddles segments runs the extension of each segment it touches with the
-// rows of the other segments pointed at a page of zeros.
+// rows of the other segments pointed at a page of zeros.  What a tile has to know about its
+// segments comes as one record per row tile (GemmTile, derived by the preparation kernel), touched
+// one tile ahead so that the fetch at the tile switch hits the scalar cache.
 //
 // Tile: 256 x 256 outputs per workgroup, 64-deep K steps (stages), 8 waves (2 along rows x 4 along
 // columns, 128 x 64 outputs each).  Operands go HBM -> LDS directly (global_load_lds, 16 bytes per
@@ -43,16 +45,25 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, v2bf));
 }
 
-// Next segment at or after `from` that overlaps rows [m0, m1), has an adapter and at least one row.
-__device__ inline int next_ext_seg(const MetaView &mv, int from, int m0, int m1)
+// Segment table walk for tiles that overlap more than the two segments spelled out in their GemmTile:
+// the next segment at or after `from` that overlaps rows [.., m1), has an adapter and at least one row.
+__device__ inline int next_ext_seg(const MetaView &mv, int n, int from, int m1)
 {
-    const int n = mv.hdr->n_seg;
     for (int s = from; s < n; ++s) {
         const int r0 = mv.seg[s].row0, r1 = mv.seg[s].row1;
         if (r0 >= m1) return n;
-        if (mv.seg[s].adapter >= 0 && r1 > r0 && r1 > m0) return s;
+        if (mv.seg[s].adapter >= 0 && r1 > r0) return s;
     }
     return n;
+}
+
+__device__ inline GemmSeg load_ext_seg(const MetaView &mv, int s)
+{
+    const SegInfo g = mv.seg[s];
+    const AdapterInfo a = mv.ad[g.adapter];
+    GemmSeg q;
+    q.row0 = g.row0; q.row1 = g.row1; q.rp = g.rp; q.r = g.r; q.hb_off = g.hb_off; q.B = a.B; q.ap_off = a.ap_off;
+    return q;
 }
 
 template <int N> __device__ inline void wait_vmcnt()
@@ -81,12 +92,17 @@ __device__ inline void wait_vmcnt_048(int n)
 }
 
 template <bool FWD>
-__global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__restrict__ S,
+__global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles, const SegInfo *__restrict__ segs,
+                                              const AdapterInfo *__restrict__ ads, const uint16_t *__restrict__ S,
                                               const uint16_t *__restrict__ W, const uint16_t *__restrict__ side,
                                               const uint16_t *__restrict__ ap, const uint16_t *__restrict__ zero,
-                                              uint16_t *__restrict__ Cout, int tiles_m, int tiles_n, int M, int d_in, int d_out)
+                                              uint16_t *__restrict__ Cout, int tiles_m, int tiles_n, int M, int d_in, int d_out, int n_seg)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
+    // the metadata pointers come one by one and restrict-qualified: that lets the compiler fetch the records through
+    // the scalar cache (a vector load would be counted, in order, with the direct-to-LDS loads of the ring)
+    MetaView mv;
+    mv.hdr = nullptr; mv.seg = segs; mv.ad = ads; mv.tile = tiles; mv.blk_seg = nullptr; mv.seg_list = nullptr;
     // shapes come as kernel arguments, so the first loads do not wait for a metadata fetch
     const int Kd = FWD ? d_in : d_out;
     const int N = FWD ? d_out : d_in;
@@ -98,16 +114,22 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
     // tiles so that the tiles resident on one XCD at a time share rows of S and columns of W.
     const int n_tiles = tiles_m * tiles_n;
     int m0 = 0, n0 = 0, m1 = 0;
-    auto set_tile = [&](int vb) {
+    auto tile_coords = [&](int vb, int &row_tile, int &col_tile) {
         int tile = vb;
         const int per = n_tiles / 8;
         if (tile < per * 8) tile = (tile % 8) * per + tile / 8;
-        constexpr int GM = 4;
+        constexpr int GM = kGemmGroupRows;
         const int group = tile / (GM * tiles_n), first = group * GM;
         const int gsz = (tiles_m - first < GM) ? tiles_m - first : GM;
         const int in = tile - group * GM * tiles_n;
-        m0 = (first + in % gsz) * BM;
-        n0 = (in / gsz) * BN;
+        row_tile = first + in % gsz;
+        col_tile = in / gsz;
+    };
+    auto set_tile = [&](int vb) {
+        int rt, ct;
+        tile_coords(vb, rt, ct);
+        m0 = rt * BM;
+        n0 = ct * BN;
         m1 = (m0 + BM < M) ? m0 + BM : M;
     };
 
@@ -156,15 +178,37 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
         base_w = reinterpret_cast<const char *>(W) + (FWD ? (int64_t)n0 * 2 : (int64_t)n0 * ldw * 2);
     };
 
-    // Stages of a tile: the main K steps, then one extension step per 64 padded rank columns of every
-    // segment with an adapter that overlaps the rows of the tile.
+    // Stages of a tile: first one extension step per 64 padded rank columns of every segment with an
+    // adapter that overlaps the rows of the tile, then the main K steps.  The extension steps come
+    // first because their operands (the low-rank factor, B_k or A_k) are cold - first touched by this
+    // tile - while the main operands stream: fetched in the prologue, their latency hides behind the
+    // stores of the previous tile instead of stalling the end of the loop.
     const int nk_main = (Kd + BK - 1) / BK;
-    int ext_seg = 0, ext_kk = 0, n_it = 0;
+    int n_it = 0;
+    // cursor over the extension steps: ext_pos = which of the tile's segments is being issued (0 and 1 are spelled
+    // out in the tile's record, from 2 on the segment table is walked: ext_walk = index of that segment), ext_kk =
+    // its next rank column, ext_left = segments not finished yet.  The record is re-read where it is used - it sits
+    // in the scalar cache by then - rather than held in registers, which this kernel has none to spare of.
+    int ext_pos = 0, ext_left = 0, ext_kk = 0, ext_walk = 0;
+    const int n_seg_all = n_seg;
     auto scan_segments = [&]() {
-        const TileExt te = mv.tile_ext[m0 / BM];   // built on the host: one load instead of a walk over the segments
-        ext_seg = te.first_seg;
+        const GemmTile *gt = mv.tile + __builtin_amdgcn_readfirstlane(m0 / BM);
+        n_it = nk_main + gt->n_ext;
+        ext_left = gt->n_own;
+        ext_walk = gt->third_seg;
+        ext_pos = 0;
         ext_kk = 0;
-        n_it = nk_main + te.n_ext;
+    };
+    auto ext_segment = [&]() -> GemmSeg {
+        const int pos = __builtin_amdgcn_readfirstlane(ext_pos);
+        if (pos < 2) return mv.tile[__builtin_amdgcn_readfirstlane(m0 / BM)].s[pos];
+        return load_ext_seg(mv, __builtin_amdgcn_readfirstlane(ext_walk));
+    };
+    auto ext_advance = [&]() {
+        ext_kk = 0;
+        ext_left -= 1;
+        if (ext_pos >= 2) ext_walk = next_ext_seg(mv, n_seg_all, ext_walk + 1, m1);   // rare: over two segments in a row tile
+        ext_pos += 1;
     };
 
     // The direct-to-LDS loads are issued through inline assembly: the compiler, which cannot tell
@@ -172,7 +216,9 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
     // for all of them (vmcnt(0)) and serialise the pipeline.  Ordering is explicit instead: a
     // counted s_waitcnt plus a bare barrier before a granule is read (__syncthreads would add a
     // fence that drains every load in flight).  M0 holds the wave-uniform LDS destination; lane i
-    // lands at M0 + 16 i.
+    // lands at M0 + 16 i.  M0 is not named as a clobber: it is a reserved register on this target (the
+    // compiler rejects it in clobber lists as undefined behaviour) in which the compiler keeps no value
+    // across statements - it writes M0 itself right in front of each of its own instructions that read it.
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
     auto load_ptr = [&](const void *g, uint32_t dst) {
         asm volatile("s_mov_b32 m0, %1\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(g), "s"(dst));
@@ -188,9 +234,10 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
     // that segment (zeros for the other rows of the tile) and B_k or the padded A_k.
     auto issue_w = [&](int it, int slot) {
         const uint32_t dst = lds_base + (w_half ? kWB : kWA) + slot * GR + w4 * 1024;
-        if (it < nk_main) {
-            const int k0 = it * BK;
-            const char *gw = base_w + (int64_t)it * step_w;
+        const int n_ext = n_it - nk_main;
+        if (it >= n_ext) {
+            const int k0 = (it - n_ext) * BK;
+            const char *gw = base_w + (int64_t)(it - n_ext) * step_w;
             if (k0 + BK <= Kd) {
 #pragma unroll
                 for (int jj = 0; jj < NL; ++jj) load_off(off_w[jj], gw, dst + jj * 4096);
@@ -201,11 +248,13 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
                     load_ptr(ok ? static_cast<const void *>(gw + off_w[jj]) : zero, dst + jj * 4096);
                 }
             }
+        } else if (ext_left <= 0) {
+            // padding step (the tile's own segments are used up): zeros
+#pragma unroll
+            for (int jj = 0; jj < NL; ++jj) load_ptr(zero, dst + jj * 4096);
         } else {
-            const int sidx = __builtin_amdgcn_readfirstlane(ext_seg);
             const int kk = __builtin_amdgcn_readfirstlane(ext_kk);
-            const SegInfo g = mv.seg[sidx];
-            const AdapterInfo a = mv.ad[g.adapter];
+            const GemmSeg es = ext_segment();
 #pragma unroll
             for (int jj = 0; jj < NL; ++jj) {
                 const uint16_t *gw;
@@ -213,11 +262,12 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
                     const int j = kk + w_half * 32 + b_row + 8 * jj;   // row of B_k
                     int n = n0 + b_chunk * 8;
                     n = n < N ? n : N - 8;
-                    gw = (j < g.r) ? static_cast<const uint16_t *>(a.B) + (int64_t)j * ldw + n : zero;
+                    // j < 128 and ldw <= 2^22: the row offset fits 32 bits
+                    gw = (j < es.r) ? static_cast<const uint16_t *>(es.B) + ((uint32_t)j * (uint32_t)ldw + (uint32_t)n) : zero;
                 } else {
                     int n = n0 + w_half * 128 + b_row + 32 * jj;       // row of padded A_k
                     n = n < N ? n : N - 1;
-                    gw = ap + a.ap_off + (int64_t)n * g.rp + kk + b_chunk * 8;
+                    gw = ap + es.ap_off + (int64_t)n * es.rp + kk + b_chunk * 8;
                 }
                 load_ptr(gw, dst + jj * 4096);
             }
@@ -225,8 +275,9 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
     };
     auto issue_x = [&](int it, int slot) {
         const uint32_t dst = lds_base + (x_half ? kXT : kXL) + slot * GR + w4 * 1024;
-        if (it < nk_main) {
-            const int k0 = it * BK;
+        const int n_ext = n_it - nk_main;
+        if (it >= n_ext) {
+            const int k0 = (it - n_ext) * BK;
             const char *gx = base_x + (int64_t)k0 * 2;
             if (k0 + BK <= Kd) {
 #pragma unroll
@@ -238,18 +289,20 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
                     load_ptr(ok ? static_cast<const void *>(gx + off_x[jj]) : zero, dst + jj * 4096);
                 }
             }
+        } else if (ext_left <= 0) {
+#pragma unroll
+            for (int jj = 0; jj < NL; ++jj) load_ptr(zero, dst + jj * 4096);
         } else {
-            const int sidx = __builtin_amdgcn_readfirstlane(ext_seg);
             const int kk = __builtin_amdgcn_readfirstlane(ext_kk);
-            const SegInfo g = mv.seg[sidx];
+            const GemmSeg es = ext_segment();
 #pragma unroll
             for (int jj = 0; jj < NL; ++jj) {
                 const int row = m0 + x_half * 128 + a_row + 32 * jj;
-                const bool in = row >= g.row0 && row < g.row1;
-                load_ptr(in ? side + g.hb_off + (int64_t)(row - g.row0) * g.rp + kk + a_chunk * 8 : zero, dst + jj * 4096);
+                const bool in = row >= es.row0 && row < es.row1;
+                load_ptr(in ? side + es.hb_off + (int64_t)(row - es.row0) * es.rp + kk + a_chunk * 8 : zero, dst + jj * 4096);
             }
             ext_kk = kk + BK;
-            if (ext_kk >= g.rp) { ext_seg = next_ext_seg(mv, sidx + 1, m0, m1); ext_kk = 0; }
+            if (ext_kk >= es.rp) ext_advance();
         }
     };
 
@@ -345,17 +398,26 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
         wait_vmcnt_048(4 * (after < 0 ? 0 : after));
     };
     // Prologue of a tile: both groups fetch their granules of stages 0 and 1 (the leading group leaves the
-    // S granule of stage 1 to its first read phase).  With two main K steps or more these loads do not
-    // depend on the segment table, which is then scanned while they are in flight.
+    // S granule of stage 1 to its first read phase).
     auto prologue = [&]() {
         set_addresses();
-        if (nk_main < 2) scan_segments();
+        scan_segments();
         issue_w(0, 0); issue_x(0, 0); gi = 2;
-        if (nk_main >= 2 || n_it > 1) {
+        if (n_it > 1) {
             issue_w(1, 1); ++gi;
             if (grp == 1) { issue_x(1, 1); ++gi; }
         }
-        if (nk_main >= 2) scan_segments();
+    };
+
+    // The record of the tile after this one is touched early in the loop (two scalar loads, one per 64-byte
+    // line), so that the fetch of it at the tile switch finds it in the scalar cache instead of waiting on L2.
+    auto touch_next_tile = [&](int vb_now) {
+        if (vb_now + (int)gridDim.x >= n_tiles) return;
+        int rt, ct;
+        tile_coords(vb_now + (int)gridDim.x, rt, ct);
+        const int32_t *p = reinterpret_cast<const int32_t *>(mv.tile + __builtin_amdgcn_readfirstlane(rt));
+        const int32_t a = p[0], b = p[16];
+        asm volatile("" ::"s"(a), "s"(b));
     };
 
     int vb = blockIdx.x;
@@ -378,6 +440,7 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
             const int xs = kXL + (s & 1) * GR, wa = kWA + s3 * GR, wb = kWB + s3 * GR;
             const int s3n = s3 == 2 ? 0 : s3 + 1, s3nn = s3n == 2 ? 0 : s3n + 1;
             // phase 4s: read half 0; fetch the trailing group's S rows of stage s+1
+            if (s == 1) touch_next_tile(vb);
             read_half(xs, wa, wb, 0);
             if (s + 1 < n_it) { issue_x(s + 1, (s + 1) & 1); ++gi; }
             __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0): operands in registers before the roles swap
@@ -404,6 +467,7 @@ __global__ void __launch_bounds__(512) k_gemm(MetaView mv, const uint16_t *__res
             const int xs = kXT + (s & 1) * GR, wa = kWA + s3 * GR, wb = kWB + s3 * GR;
             const int s3n = s3 == 2 ? 0 : s3 + 1, s3nn = s3n == 2 ? 0 : s3n + 1;
             // phase 4s+1: read half 0; fetch the first W half of stage s+2
+            if (s == 1) touch_next_tile(vb);
             read_half(xs, wa, wb, 0);
             if (s + 2 < n_it) { issue_w(s + 2, s3nn); ++gi; }
             __builtin_amdgcn_s_waitcnt(0xc07f);
@@ -472,27 +536,20 @@ static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, const 
     const int64_t N = FWD ? h.K : h.D;
     const int tiles_m = (int)((h.T + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     auto kern = k_gemm<FWD>;
-    static bool attr_done = false;
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, kGemmLds);
+    {
+        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(kern), FWD ? 5 : 6);
         if (e != hipSuccess) return e;
-        attr_done = true;
     }
     // persistent grid: one workgroup per compute unit (256 on an MI355X; a workgroup takes a whole CU's LDS)
-    static int n_cu = 0;
-    if (n_cu == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || v < 1)
-            return hipErrorInvalidDevice;
-        n_cu = v;
-    }
+    hipError_t cu_err = hipSuccess;
+    const int n_cu = device_cu_count(&cu_err);
+    if (n_cu < 1) return cu_err;
     const int n_tiles = tiles_m * tiles_n;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < n_cu ? n_tiles : n_cu)), dim3(512), kGemmLds, st, mv,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < n_cu ? n_tiles : n_cu)), dim3(512), kGemmLds, st, mv.tile, mv.seg, mv.ad,
                        static_cast<const uint16_t *>(S), static_cast<const uint16_t *>(W),
                        static_cast<const uint16_t *>(side), static_cast<const uint16_t *>(ap),
                        static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n, (int)h.T, (int)h.D,
-                       (int)h.K);
+                       (int)h.K, (int)h.n_seg);
     return hipGetLastError();
 }
 

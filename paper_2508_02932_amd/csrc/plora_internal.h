@@ -17,6 +17,19 @@ constexpr int kTokPad = 64;        // segment lengths are padded to this in the 
 constexpr int kZeroBytes = 1024;   // zero page at the head of the workspace
 constexpr int kTokMaxSplits = 8;    // the dA / dB kernels split the token walk over at most this many workgroups
 constexpr int kSkinnyMaxSplits = 8; // the skinny kernels split the contraction over at most this many workgroups
+constexpr int kGemmTileRows = 256;  // row tile of the base GEMMs
+constexpr int kGemmGroupRows = 4;   // row tiles that the GEMM's tile order keeps together on one XCD (they share W columns in its L2)
+
+// ---------------------------------------------------------------------------------------------
+// Segment-packing metadata (section 2.4: which rows belong to which adapter).
+//
+// The host validates the description and ships it to the device in a compact form (a few 32-bit
+// words per segment and adapter, passed by value as a kernel argument).  The tables the kernels
+// read are derived from it by one set of routines (derive_phase1..3) compiled for both sides: the
+// device runs them inside the preparation kernel and writes the tables into the workspace; the
+// host runs the very same code to size the workspace, to plan the launches and to export the
+// tables for the brute-force tests.
+// ---------------------------------------------------------------------------------------------
 
 // One entry per segment of the call (empty and base-only segments included).
 struct SegInfo {
@@ -46,6 +59,8 @@ struct AdapterInfo {
     int32_t by_tokens;    // entry i: the adapter with the i-th largest token count (ties by index)
     int32_t seg_list0;    // this adapter's non-empty segments: seg_list[seg_list0 .. seg_list0 + n_own), in segment order
     int32_t n_own;
+    int32_t tokens;       // tokens of this adapter over all its segments
+    int32_t reserved;
 };
 
 struct MetaHeader {
@@ -55,46 +70,304 @@ struct MetaHeader {
     int32_t max_r16;      // largest rank (padded to 16) among segments with tokens
 };
 
-// One entry per 256-row tile of the base GEMMs: the low-rank extension steps of that tile.
-constexpr int kGemmTileRows = 256;
-struct TileExt {
-    int32_t first_seg;    // first segment with an adapter and rows that overlaps the tile (n_seg if none)
-    int32_t n_ext;        // extension steps of the tile: sum over such segments of rp / 64
+// What a 256-row tile of the base GEMMs needs to know about one segment whose low-rank term it adds.
+struct GemmSeg {
+    int32_t row0, row1;   // rows of the segment
+    int32_t rp, r;        // padded and true rank
+    int64_t hb_off;       // element offset of the segment in the bf16 low-rank factor [len][rp]
+    const void *B;        // forward: B_k [r][d_out]
+    int64_t ap_off;       // backward: element offset of padded A_k [d_in][rp]
 };
 
-// Device view of the metadata blob (all pointers into the workspace).  Blob layout: header, seg[n_seg],
-// ad[n_adapters], tile_ext[ceil(T / 256)], blk_seg[n_blocks], seg_list[non-empty segments with an adapter].
+// One entry per 256-row tile of the base GEMMs.  The low-rank term enters the GEMM as extra steps of
+// the contraction loop, one per 64 padded rank columns of every segment with an adapter that
+// overlaps the tile.  The first two such segments are spelled out, so that a tile gets all it needs
+// with one fetch, issued a whole tile ahead.
+struct GemmTile {
+    int32_t n_ext;        // extension steps the tile runs: the largest own count among the row tiles of its group of
+                          // kGemmGroupRows (steps beyond the tile's own segments multiply zeros), so that the workgroups
+                          // of an XCD stay in step along the contraction and keep hitting each other's lines in its L2
+    int32_t n_own;        // segments with an adapter and rows that overlap the tile
+    int32_t first_seg;    // the first of them (n_seg if none)
+    int32_t third_seg;    // the third of them (n_seg if fewer): where the walk over the segment table resumes
+    GemmSeg s[2];
+};
+
+// Device view of the derived tables (all pointers into the workspace, laid out by table_layout).
 struct MetaView {
     const MetaHeader *hdr;
     const SegInfo *seg;
     const AdapterInfo *ad;
-    const TileExt *tile_ext;
+    const GemmTile *tile;     // one per 256-row tile
     const int32_t *blk_seg;   // segment of each token block of kSkinnyRows rows
     const int32_t *seg_list;  // non-empty segments grouped by adapter (see AdapterInfo)
 };
 
+// ---- compact description -----------------------------------------------------------------------
+// 32-bit words: [0,1] T  [2,3] D  [4,5] K  [6] n_seg  [7] n_adapters  [8] n_blocks (computed by the host, fixes the
+// table layout)  [9] reserved; then per segment {row1, adapter}; then per adapter {A lo, A hi, B lo, B hi, dA lo,
+// dA hi, dB lo, dB hi, r, scale bits}.
+constexpr int kDescHeadWords = 10, kDescSegWords = 2, kDescAdWords = 10;
+constexpr int kChunkWords = 896;   // 3584 bytes: what one launch carries by value, below the 4 KB kernel-argument limit
+struct DescChunk { uint32_t w[kChunkWords]; };
+
+#define PLORA_HD __host__ __device__ inline
+
+PLORA_HD int desc_words(int n_seg, int n_adapters) { return kDescHeadWords + kDescSegWords * n_seg + kDescAdWords * n_adapters; }
+
+// Where the compact description lies: word(i) returns word i.
+struct WordsInMemory {
+    const uint32_t *p;
+    PLORA_HD uint32_t word(int i) const { return p[i]; }
+};
+
+template <class Src> struct DescReader {
+    Src src;
+    PLORA_HD int64_t w64(int i) const { return (int64_t)((uint64_t)src.word(i) | ((uint64_t)src.word(i + 1) << 32)); }
+    PLORA_HD int64_t T() const { return w64(0); }
+    PLORA_HD int64_t D() const { return w64(2); }
+    PLORA_HD int64_t K() const { return w64(4); }
+    PLORA_HD int n_seg() const { return (int)src.word(6); }
+    PLORA_HD int n_adapters() const { return (int)src.word(7); }
+    PLORA_HD int n_blocks() const { return (int)src.word(8); }
+    PLORA_HD int seg_row1(int s) const { return (int)src.word(kDescHeadWords + kDescSegWords * s); }
+    PLORA_HD int seg_row0(int s) const { return s ? seg_row1(s - 1) : 0; }
+    PLORA_HD int seg_adapter(int s) const { return (int)src.word(kDescHeadWords + kDescSegWords * s + 1); }
+    PLORA_HD int ad_base(int k) const { return kDescHeadWords + kDescSegWords * n_seg() + kDescAdWords * k; }
+    PLORA_HD const void *ad_ptr(int k, int which) const { return reinterpret_cast<const void *>((uintptr_t)w64(ad_base(k) + 2 * which)); }
+    PLORA_HD int ad_rank(int k) const { return (int)src.word(ad_base(k) + 8); }
+    PLORA_HD float ad_scale(int k) const
+    {
+        union { uint32_t u; float f; } c;
+        c.u = src.word(ad_base(k) + 9);
+        return c.f;
+    }
+};
+
+PLORA_HD int32_t pad_to(int32_t v, int32_t a) { return (v + a - 1) / a * a; }
+PLORA_HD size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Byte offsets of the derived tables inside the metadata region of the workspace.
+struct TableLayout {
+    size_t hdr, seg, ad, tile, blk_seg, seg_list, bytes;
+    int64_t n_tiles;
+};
+
+PLORA_HD TableLayout table_layout(int64_t T, int n_seg, int n_adapters, int n_blocks)
+{
+    TableLayout l;
+    size_t o = 0;
+    l.n_tiles = (T + kGemmTileRows - 1) / kGemmTileRows;
+    l.hdr = o;      o = align_up(o + sizeof(MetaHeader), 64);
+    l.seg = o;      o = align_up(o + (size_t)n_seg * sizeof(SegInfo), 64);
+    l.ad = o;       o = align_up(o + (size_t)n_adapters * sizeof(AdapterInfo), 64);
+    l.tile = o;     o = align_up(o + (size_t)l.n_tiles * sizeof(GemmTile), 64);
+    l.blk_seg = o;  o = align_up(o + (size_t)n_blocks * sizeof(int32_t), 64);
+    l.seg_list = o; o = align_up(o + (size_t)n_seg * sizeof(int32_t), 64);
+    l.bytes = o;
+    return l;
+}
+
+// Mutable pointers to the tables (a host buffer or the workspace).
+struct Tables {
+    MetaHeader *hdr;
+    SegInfo *seg;
+    AdapterInfo *ad;
+    GemmTile *tile;
+    int32_t *blk_seg;
+    int32_t *seg_list;
+};
+
+PLORA_HD Tables tables_at(char *base, const TableLayout &l)
+{
+    Tables t;
+    t.hdr = reinterpret_cast<MetaHeader *>(base + l.hdr);
+    t.seg = reinterpret_cast<SegInfo *>(base + l.seg);
+    t.ad = reinterpret_cast<AdapterInfo *>(base + l.ad);
+    t.tile = reinterpret_cast<GemmTile *>(base + l.tile);
+    t.blk_seg = reinterpret_cast<int32_t *>(base + l.blk_seg);
+    t.seg_list = reinterpret_cast<int32_t *>(base + l.seg_list);
+    return t;
+}
+
+PLORA_HD MetaView view_of(const Tables &t)
+{
+    MetaView v;
+    v.hdr = t.hdr; v.seg = t.seg; v.ad = t.ad; v.tile = t.tile; v.blk_seg = t.blk_seg; v.seg_list = t.seg_list;
+    return v;
+}
+
+// ---- derivation of the tables, in three phases ----------------------------------------------------
+// Phase 1 runs on one thread (prefix sums over adapters and segments); phases 2 and 3 are loops
+// "for (i = tid; i < n; i += nthreads)" over independent entries.  A phase reads what the phases before it wrote, so
+// the caller separates them with a barrier (device: one workgroup, __syncthreads; host: tid 0 of 1, nothing to do).
+
+template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, const Tables &t)
+{
+    const int n_seg = in.n_seg(), n_ad = in.n_adapters();
+    const int64_t D = in.D();
+    int64_t at = 0, ap = 0;
+    int32_t r16_off = 0;
+    for (int k = 0; k < n_ad; ++k) {
+        AdapterInfo a;
+        a.A = in.ad_ptr(k, 0);
+        a.B = in.ad_ptr(k, 1);
+        a.dA = static_cast<float *>(const_cast<void *>(in.ad_ptr(k, 2)));
+        a.dB = static_cast<float *>(const_cast<void *>(in.ad_ptr(k, 3)));
+        a.r = in.ad_rank(k);
+        a.rp = pad_to(a.r, kRankPadGemm);
+        a.r16 = pad_to(a.r, kRankPadMfma);
+        a.scale = in.ad_scale(k);
+        a.at_off = at; at += (int64_t)a.r16 * D;
+        a.ap_off = ap; ap += (int64_t)a.rp * D;
+        a.r16_off = r16_off; r16_off += a.r16;
+        a.by_tokens = 0; a.seg_list0 = 0; a.n_own = 0; a.tokens = 0; a.reserved = 0;
+        t.ad[k] = a;
+    }
+    int64_t h = 0, hb = 0, zt = 0;
+    int32_t blk = 0, max_r16 = 0, row0 = 0;
+    for (int s = 0; s < n_seg; ++s) {
+        SegInfo g;
+        g.row0 = row0; g.row1 = in.seg_row1(s); row0 = g.row1;
+        g.adapter = in.seg_adapter(s);
+        const int32_t len = g.row1 - g.row0;
+        const int32_t r = g.adapter >= 0 ? in.ad_rank(g.adapter) : 0;
+        g.r = r;
+        g.rp = pad_to(r, kRankPadGemm);
+        g.r16 = pad_to(r, kRankPadMfma);
+        g.lp = pad_to(len, kTokPad);
+        g.blk0 = blk;
+        g.h_off = h; g.hb_off = hb; g.zt_off = zt;
+        if (g.adapter >= 0) {
+            blk += (len + kSkinnyRows - 1) / kSkinnyRows;
+            if (len > 0 && g.r16 > max_r16) max_r16 = g.r16;
+            h += (int64_t)len * g.r;
+            hb += (int64_t)len * g.rp;
+            zt += (int64_t)g.r16 * g.lp;
+            t.ad[g.adapter].tokens += len;
+            t.ad[g.adapter].n_own += len > 0;
+        }
+        t.seg[s] = g;
+    }
+    // per-adapter lists of non-empty segments, in segment order
+    int32_t o = 0;
+    for (int k = 0; k < n_ad; ++k) { t.ad[k].seg_list0 = o; t.ad[k].reserved = o; o += t.ad[k].n_own; }
+    for (int s = 0; s < n_seg; ++s) {
+        const int a = t.seg[s].adapter;
+        if (a >= 0 && t.seg[s].row1 > t.seg[s].row0) t.seg_list[t.ad[a].reserved++] = s;
+    }
+    for (int k = 0; k < n_ad; ++k) t.ad[k].reserved = 0;
+    MetaHeader hd;
+    hd.T = in.T(); hd.D = D; hd.K = in.K();
+    hd.n_seg = n_seg; hd.n_adapters = n_ad; hd.n_blocks = blk; hd.max_r16 = max_r16;
+    *t.hdr = hd;
+}
+
+PLORA_HD bool seg_has_lowrank(const SegInfo &g) { return g.adapter >= 0 && g.row1 > g.row0; }
+
+// The segment that holds token block `blk` (only segments with an adapter and rows own blocks).
+PLORA_HD int seg_of_block(const SegInfo *seg, int n_seg, int blk)
+{
+    int lo = 0, hi = n_seg - 1;                 // last segment with blk0 <= blk
+    while (lo < hi) {
+        const int mid = (lo + hi + 1) / 2;
+        if (seg[mid].blk0 <= blk) lo = mid; else hi = mid - 1;
+    }
+    // blk < n_blocks lies in some owner o (o.blk0 <= blk < o.blk0 + blocks of o); every later segment starts at or
+    // behind the end of o's blocks, so the last segment with blk0 <= blk is o itself
+    return lo;
+}
+
+// Own extension steps and the first segments of one GEMM row tile (n_ext is left at the own count).
+PLORA_HD void derive_tile(const Tables &t, int n_seg, int64_t T, int64_t tile)
+{
+    const int64_t m0 = tile * kGemmTileRows;
+    const int64_t m1 = m0 + kGemmTileRows < T ? m0 + kGemmTileRows : T;
+    int lo = 0, hi = n_seg;                     // first segment with row1 > m0
+    while (lo < hi) {
+        const int mid = (lo + hi) / 2;
+        if (t.seg[mid].row1 > m0) hi = mid; else lo = mid + 1;
+    }
+    GemmTile gt;
+    gt.n_ext = 0; gt.n_own = 0; gt.first_seg = n_seg; gt.third_seg = n_seg;
+    for (int i = 0; i < 2; ++i) {
+        gt.s[i].row0 = 0; gt.s[i].row1 = 0; gt.s[i].rp = 0; gt.s[i].r = 0;
+        gt.s[i].hb_off = 0; gt.s[i].B = nullptr; gt.s[i].ap_off = 0;
+    }
+    for (int s = lo; s < n_seg && t.seg[s].row0 < m1; ++s) {
+        const SegInfo &g = t.seg[s];
+        if (!seg_has_lowrank(g)) continue;
+        if (gt.n_own < 2) {
+            GemmSeg &q = gt.s[gt.n_own];
+            q.row0 = g.row0; q.row1 = g.row1; q.rp = g.rp; q.r = g.r; q.hb_off = g.hb_off;
+            q.B = t.ad[g.adapter].B; q.ap_off = t.ad[g.adapter].ap_off;
+            if (gt.n_own == 0) gt.first_seg = s;
+        } else if (gt.n_own == 2) {
+            gt.third_seg = s;
+        }
+        gt.n_own += 1;
+        gt.n_ext += g.rp / kRankPadGemm;
+    }
+    t.tile[tile] = gt;
+}
+
+PLORA_HD void derive_phase2(const Tables &t, int tid, int nthreads)
+{
+    const int n_seg = t.hdr->n_seg, n_ad = t.hdr->n_adapters, n_blocks = t.hdr->n_blocks;
+    const int64_t T = t.hdr->T;
+    const int64_t n_tiles = (T + kGemmTileRows - 1) / kGemmTileRows;
+    for (int b = tid; b < n_blocks; b += nthreads) t.blk_seg[b] = seg_of_block(t.seg, n_seg, b);
+    for (int64_t tile = tid; tile < n_tiles; tile += nthreads) derive_tile(t, n_seg, T, tile);
+    // place of each adapter in the order by token count, longest first (the weight-gradient kernels hand out
+    // adapters in that order, so the last workgroups are short)
+    for (int k = tid; k < n_ad; k += nthreads) {
+        const int32_t mine = t.ad[k].tokens;
+        int rank = 0;
+        for (int j = 0; j < n_ad; ++j) {
+            const int32_t theirs = t.ad[j].tokens;
+            if (theirs > mine || (theirs == mine && j < k)) ++rank;
+        }
+        t.ad[rank].by_tokens = k;
+    }
+}
+
+PLORA_HD void derive_phase3(const Tables &t, int tid, int nthreads)
+{
+    // equal step counts inside a group of row tiles; one thread per group, so nobody reads a count already raised
+    const int64_t n_tiles = (t.hdr->T + kGemmTileRows - 1) / kGemmTileRows;
+    const int64_t n_groups = (n_tiles + kGemmGroupRows - 1) / kGemmGroupRows;
+    for (int64_t grp = tid; grp < n_groups; grp += nthreads) {
+        const int64_t t0 = grp * kGemmGroupRows, t1 = t0 + kGemmGroupRows < n_tiles ? t0 + kGemmGroupRows : n_tiles;
+        int32_t mx = 0;
+        for (int64_t q = t0; q < t1; ++q) mx = t.tile[q].n_ext > mx ? t.tile[q].n_ext : mx;
+        for (int64_t q = t0; q < t1; ++q) t.tile[q].n_ext = mx;
+    }
+}
+
 // Byte offsets of the workspace regions, each 256-byte aligned.
 struct WorkspaceLayout {
-    size_t zero, meta, at, ap, hb, zt_h, zt_g, hf, gf, part, wpart, total;
+    size_t zero, meta, desc, at, ap, hb, zt_h, zt_g, hf, gf, part, wpart, total;
     size_t meta_bytes;
 };
 
-struct KernelTimer;   // bench-only event bracketing, see plora_api.hip
-
 // ---- launch wrappers implemented in the kernel files; all enqueue on `st` and return the HIP status ----
 
-hipError_t upload_blob(void *dst_dev, const void *src_host, size_t bytes, hipStream_t st);
-hipError_t clear_zero_page(void *zero_dev, hipStream_t st);
-// One launch for blob + zero page + packing of A_k + transposed copy of a saved activation (each optional);
-// only when prep_fits(blob_bytes).
-bool prep_fits(size_t blob_bytes);
-hipError_t launch_prep(const MetaHeader &h, void *meta_dev, const void *blob_host, size_t blob_bytes, void *zero_dev,
-                       void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt, hipStream_t st);
+// Compute units of the current device (thread-safe, looked up once per device); 0 with *err set on failure.
+int device_cu_count(hipError_t *err);
+// Lets `kernel` use up to the 160 KB of LDS of a compute unit; done once per device and kernel (slot: a small
+// index that is unique per kernel), thread-safe.
+hipError_t allow_full_lds(const void *kernel, int slot);
+constexpr int kLdsSlots = 16;
+
+// Metadata and the small jobs in front of the heavy kernels, in one launch when the compact description fits a
+// kernel argument (otherwise it is first uploaded in chunks to desc_stage): derived tables and zero page into the
+// workspace; packing of A_k (bf16 path: A_k^T [r16][d_in] with zero rows beyond r, and / or A_k padded to rp
+// columns); transposed bf16 copy of a saved activation, zt[j][t] = bf16(h[t][j]) (bf16 backward).
+hipError_t launch_prep(const uint32_t *desc_host, int n_words, const MetaHeader &h, char *meta_dev, uint32_t *desc_stage,
+                       void *zero_dev, void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt,
+                       hipStream_t st);
 
 // bf16 path -------------------------------------------------------------------------------------
-// Packs A_k^T (zero rows beyond r) and/or A_k padded to rp columns.
-hipError_t launch_pack_bf16(const MetaView &mv, const MetaHeader &h, void *at, void *ap, bool want_at,
-                            bool want_ap, hipStream_t st);
 // Skinny product over token blocks: acc[t][j] = sum_c S[t][c] * Bm_k[j][c]  (c < C).
 //   mode 0 (shrink): S = x (C = d_in), Bm_k = packed A_k^T;  mode 1 (dH): S = dy (C = d_out), Bm_k = B_k.
 //   `part` receives the fp32 partial tiles of the contraction splits; a finishing kernel sums them and
@@ -103,8 +376,6 @@ hipError_t launch_pack_bf16(const MetaView &mv, const MetaHeader &h, void *at, v
 hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode, const void *S, int64_t C,
                               const void *at, const void *zero, float *part, float *hf, void *hb, void *zt,
                               bool zt_scaled, hipStream_t st);
-// Transposed bf16 copy of a saved fp32 activation: zt[j][t] = bf16(h[t][j]).
-hipError_t launch_h_to_zt(const MetaView &mv, const MetaHeader &h, const float *hf, void *zt, hipStream_t st);
 // C[T][N] = S[T][Kd] * Wop + side[T][rp] * ext_k, rounded to bf16.
 //   forward : S = x,  Wop = W [Kd=d_in][N=d_out] (contraction index is the row index), ext_k = B_k [r][N]
 //   backward: S = dy, Wop = W [N=d_in][Kd=d_out] (contraction index is contiguous),    ext_k = padded A_k [N][rp]
@@ -117,6 +388,7 @@ hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool
                                    int64_t C, const void *zt, const void *zero, float *part, int n_split,
                                    int r16_total, int n_active_adapters, hipStream_t st);
 int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters);
+int tokc_tile_columns(const MetaHeader &h, int64_t C, int n_active_adapters);
 int skinny_splits(const MetaHeader &h, int64_t C);
 
 // fp32 path (fp64 accumulation) ---------------------------------------------------------------------

@@ -263,12 +263,9 @@ hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode,
     const int n_stage_all = (int)((C + SK_BK - 1) / SK_BK);
     const int per = (n_stage_all + n_split - 1) / n_split;
     const size_t lds = (size_t)SK_NST * (SK_XT + h.max_r16 * SK_BK * 2);
-    static size_t lds_allowed = 0;
-    if (lds > lds_allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_skinny),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(k_skinny), 0);
         if (e != hipSuccess) return e;
-        lds_allowed = lds;
     }
     hipLaunchKernelGGL(k_skinny, dim3((unsigned)h.n_blocks, (unsigned)n_split), dim3(64 * SK_NW), lds, st, mv, mode,
                        static_cast<const uint16_t *>(S), (int)C, static_cast<const uint16_t *>(at),

@@ -1,50 +1,67 @@
-// Small helper kernels of libplora: metadata upload through kernel arguments, zero page, packing
-// of the adapter matrices into MFMA-friendly bf16 buffers, transposed copy of a saved activation.
+// Small helper kernels of libplora: derivation of the metadata tables from the compact description
+// (which travels as a kernel argument), zero page, packing of the adapter matrices into
+// MFMA-friendly bf16 buffers, transposed copy of a saved activation.
 #include "plora_internal.h"
 
 #include <cstring>
+#include <mutex>
 
 namespace plora {
 
-// ---- metadata upload -------------------------------------------------------------------------
-// The blob travels as a by-value kernel argument, so the host copy is consumed at launch time
-// and no pinned staging buffer or host-to-device copy is needed (the call stays capturable).
-constexpr int kChunkWords = 896;   // 3584 bytes per launch, below the 4 KB kernel-argument limit
-struct BlobChunk { uint32_t w[kChunkWords]; };
+// ---- per-device state ---------------------------------------------------------------------------
+constexpr int kMaxDevices = 64;
+static std::mutex g_dev_mu;
+static int g_cu[kMaxDevices];
+static bool g_lds_ok[kMaxDevices][kLdsSlots];
 
-__global__ void __launch_bounds__(256) k_upload(BlobChunk c, uint32_t *dst, int n_words)
+int device_cu_count(hipError_t *err)
 {
-    for (int i = threadIdx.x; i < n_words; i += 256) dst[i] = c.w[i];
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess || dev < 0 || dev >= kMaxDevices) { *err = e != hipSuccess ? e : hipErrorInvalidDevice; return 0; }
+    std::lock_guard<std::mutex> lock(g_dev_mu);
+    if (g_cu[dev] == 0) {
+        int v = 0;
+        e = hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess || v < 1) { *err = e != hipSuccess ? e : hipErrorInvalidDevice; return 0; }
+        g_cu[dev] = v;
+    }
+    *err = hipSuccess;
+    return g_cu[dev];
 }
 
-hipError_t upload_blob(void *dst_dev, const void *src_host, size_t bytes, hipStream_t st)
+hipError_t allow_full_lds(const void *kernel, int slot)
 {
-    const size_t words = (bytes + 3) / 4;
-    const char *src = static_cast<const char *>(src_host);
-    for (size_t w0 = 0; w0 < words; w0 += kChunkWords) {
-        BlobChunk c;
-        const size_t nw = (words - w0 < (size_t)kChunkWords) ? words - w0 : (size_t)kChunkWords;
-        const size_t b0 = w0 * 4;
-        const size_t nb = (bytes - b0 < nw * 4) ? bytes - b0 : nw * 4;
-        std::memset(&c, 0, sizeof(c));
-        std::memcpy(c.w, src + b0, nb);
-        hipLaunchKernelGGL(k_upload, dim3(1), dim3(256), 0, st, c, static_cast<uint32_t *>(dst_dev) + w0, (int)nw);
-        hipError_t e = hipGetLastError();
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices || slot < 0 || slot >= kLdsSlots) return hipErrorInvalidValue;
+    std::lock_guard<std::mutex> lock(g_dev_mu);
+    if (!g_lds_ok[dev][slot]) {
+        e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
         if (e != hipSuccess) return e;
+        g_lds_ok[dev][slot] = true;
     }
     return hipSuccess;
 }
 
-__global__ void __launch_bounds__(256) k_zero_page(uint32_t *p)
+// ---- chunked upload of a compact description too long for one kernel argument ----------------------
+__global__ void __launch_bounds__(256) k_upload(DescChunk c, uint32_t *dst, int n_words)
 {
-    p[threadIdx.x] = 0u;   // kZeroBytes = 256 * 4
+    for (int i = threadIdx.x; i < n_words; i += 256) dst[i] = c.w[i];
 }
 
-hipError_t clear_zero_page(void *zero_dev, hipStream_t st)
+static hipError_t upload_words(uint32_t *dst_dev, const uint32_t *src_host, int n_words, hipStream_t st)
 {
-    static_assert(kZeroBytes == 1024, "zero page is written by one 256-thread block");
-    hipLaunchKernelGGL(k_zero_page, dim3(1), dim3(256), 0, st, static_cast<uint32_t *>(zero_dev));
-    return hipGetLastError();
+    for (int w0 = 0; w0 < n_words; w0 += kChunkWords) {
+        DescChunk c;
+        const int nw = n_words - w0 < kChunkWords ? n_words - w0 : kChunkWords;
+        std::memcpy(c.w, src_host + w0, (size_t)nw * 4);
+        hipLaunchKernelGGL(k_upload, dim3(1), dim3(256), 0, st, c, dst_dev + w0, nw);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 // ---- packing of A_k ------------------------------------------------------------------------------
@@ -53,7 +70,13 @@ hipError_t clear_zero_page(void *zero_dev, hipStream_t st)
 // ap: A_k as [D][rp] with columns j >= r zero - the low-rank K-extension operand of the dX GEMM.
 // One block handles 64 rows i of one adapter; the tile goes through LDS so that both the reads of
 // A_k (contiguous in j) and the writes of A_k^T (contiguous in i) are coalesced.
-__device__ inline void pack_block(const AdapterInfo &a, int64_t D, int bx, uint16_t *at, uint16_t *ap, int want_at,
+struct PackJob {
+    const uint16_t *A;
+    int r, rp, r16;
+    int64_t at_off, ap_off;
+};
+
+__device__ inline void pack_block(const PackJob &a, int64_t D, int bx, uint16_t *at, uint16_t *ap, int want_at,
                                   int want_ap, uint16_t *tile)
 {
     // The 64 rows of A_k handled here are one contiguous slab of 64 r elements: copy it to LDS as it is
@@ -61,11 +84,10 @@ __device__ inline void pack_block(const AdapterInfo &a, int64_t D, int bx, uint1
     const int64_t i0 = (int64_t)bx * 64;
     const int r = a.r;
     const int rows = (int)((D - i0 < 64) ? D - i0 : 64);
-    const uint4 *src = reinterpret_cast<const uint4 *>(static_cast<const uint16_t *>(a.A) + i0 * r);
+    const uint4 *src = reinterpret_cast<const uint4 *>(a.A + i0 * r);
     const int n_vec = rows * r / 8;                    // r * 2 bytes * rows is a multiple of 16 when rows == 64
     for (int v = threadIdx.x; v < n_vec; v += 256) reinterpret_cast<uint4 *>(tile)[v] = src[v];
-    for (int e = n_vec * 8 + threadIdx.x; e < rows * r; e += 256)
-        tile[e] = static_cast<const uint16_t *>(a.A)[i0 * r + e];
+    for (int e = n_vec * 8 + threadIdx.x; e < rows * r; e += 256) tile[e] = a.A[i0 * r + e];
     __syncthreads();
     if (want_at) {
         // A_k^T rows j: 64 consecutive elements each; a wave writes one row segment of 128 bytes
@@ -89,23 +111,6 @@ __device__ inline void pack_block(const AdapterInfo &a, int64_t D, int bx, uint1
     }
 }
 
-__global__ void __launch_bounds__(256) k_pack_a(MetaView mv, uint16_t *at, uint16_t *ap, int want_at, int want_ap)
-{
-    __shared__ __attribute__((aligned(16))) uint16_t tile[64 * PLORA_MAX_RANK];
-    const AdapterInfo a = mv.ad[blockIdx.y];
-    pack_block(a, mv.hdr->D, blockIdx.x, at, ap, want_at, want_ap, tile);
-}
-
-hipError_t launch_pack_bf16(const MetaView &mv, const MetaHeader &h, void *at, void *ap, bool want_at,
-                            bool want_ap, hipStream_t st)
-{
-    if (h.n_adapters == 0 || (!want_at && !want_ap)) return hipSuccess;
-    dim3 grid((unsigned)((h.D + 63) / 64), (unsigned)h.n_adapters);
-    hipLaunchKernelGGL(k_pack_a, grid, dim3(256), 0, st, mv, static_cast<uint16_t *>(at),
-                       static_cast<uint16_t *>(ap), want_at ? 1 : 0, want_ap ? 1 : 0);
-    return hipGetLastError();
-}
-
 // ---- transposed bf16 copy of a saved fp32 activation ------------------------------------------------
 __device__ inline uint16_t f32_to_bf16_rne(float f)
 {
@@ -114,14 +119,19 @@ __device__ inline uint16_t f32_to_bf16_rne(float f)
     return (uint16_t)(u >> 16);
 }
 
-// zt[j][t] = bf16(h[t][j]); rows j >= r and the padding tokens are written as zero.  Grid: (token
-// block of kSkinnyRows rows, slice of 16 rows inside it).
-__device__ inline void h_to_zt_slice(const SegInfo &g, int blk, int slice, const float *hf, uint16_t *zt, float *tile)
+// zt[j][t] = bf16(h[t][j]); rows j >= r and the padding tokens are written as zero.  One workgroup per
+// (token block of kSkinnyRows rows, slice of 16 rows inside it).
+struct TransposeJob {
+    int len, r, r16, lp, t_block;    // segment length and rank; first token of the block inside the segment
+    int64_t h_off, zt_off;
+};
+
+__device__ inline void h_to_zt_slice(const TransposeJob &g, int slice, const float *hf, uint16_t *zt, float *tile)
 {
     constexpr int FR = 16;
-    const int t0 = (blk - g.blk0) * kSkinnyRows + slice * FR;   // first token of the slice inside the segment
+    const int t0 = g.t_block + slice * FR;          // first token of the slice inside the segment
     if (t0 >= g.lp) return;
-    int nt = g.row1 - g.row0 - t0;
+    int nt = g.len - t0;
     nt = nt < 0 ? 0 : (nt < FR ? nt : FR);
     // the nt rows of r floats are contiguous: flat copy, then transposed reads (thread -> rank row j, token tt)
     const float *src = hf + g.h_off + (int64_t)t0 * g.r;
@@ -133,84 +143,128 @@ __device__ inline void h_to_zt_slice(const SegInfo &g, int blk, int slice, const
         dst[(int64_t)j * g.lp + tt] = (j < g.r && tt < nt) ? f32_to_bf16_rne(tile[tt * g.r + j]) : (uint16_t)0;
 }
 
-__global__ void __launch_bounds__(256) k_h_to_zt(MetaView mv, const float *hf, uint16_t *zt)
-{
-    __shared__ float tile[16 * PLORA_MAX_RANK];
-    const int blk = blockIdx.x;
-    const SegInfo g = mv.seg[mv.blk_seg[blk]];
-    h_to_zt_slice(g, blk, blockIdx.y, hf, zt, tile);
-}
+// ---- the preparation kernel ----------------------------------------------------------------------
+// Workgroup 0 derives the metadata tables into the workspace and clears the zero page; the next
+// n_pack workgroups pack the adapter matrices; the last ones make the transposed bf16 copy of a saved
+// activation.  The packing and copy workgroups work out the few offsets they need from the compact
+// description themselves, so they do not wait for workgroup 0.
+struct WordsInArg {
+    const DescChunk &c;
+    __device__ inline uint32_t word(int i) const { return c.w[i]; }
+};
 
-hipError_t launch_h_to_zt(const MetaView &mv, const MetaHeader &h, const float *hf, void *zt, hipStream_t st)
+template <class Src>
+__device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint32_t *zero_page, uint16_t *at, uint16_t *ap,
+                                 int want_at, int want_ap, int pack_bx, int n_pack, const float *hf, uint16_t *zt,
+                                 void *shared_mem)
 {
-    if (h.n_blocks == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_h_to_zt, dim3((unsigned)h.n_blocks, kSkinnyRows / 16), dim3(256), 0, st, mv, hf, static_cast<uint16_t *>(zt));
-    return hipGetLastError();
-}
-
-// ---- fused preparation ---------------------------------------------------------------------------
-// When the whole metadata blob fits one kernel-argument chunk, a single launch does all the small
-// jobs that precede the heavy kernels: block 0 writes the blob and the zero page, the next blocks
-// pack the adapter matrices, the last ones make the transposed bf16 copy of a saved activation.
-// The packing and copy blocks read the metadata from the kernel argument itself, so they do not wait
-// for block 0.
-template <typename T> __device__ inline T read_arg(const BlobChunk &c, int byte_off)
-{
-    static_assert(sizeof(T) % 4 == 0, "metadata structs are made of 32-bit words");
-    union { T v; uint32_t w[sizeof(T) / 4]; } u;
-#pragma unroll
-    for (int i = 0; i < (int)(sizeof(T) / 4); ++i) u.w[i] = c.w[byte_off / 4 + i];
-    return u.v;
-}
-
-__global__ void __launch_bounds__(256) k_prep(BlobChunk c, uint32_t *meta_dst, int n_words, uint32_t *zero_page,
-                                             uint16_t *at, uint16_t *ap, int want_at, int want_ap, int pack_bx,
-                                             int n_pack, const float *hf, uint16_t *zt)
-{
-    __shared__ __attribute__((aligned(16))) union {
-        uint16_t pack[64 * PLORA_MAX_RANK];
-        float tr[16 * PLORA_MAX_RANK];
-    } sh;
     int b = blockIdx.x;
     if (b == 0) {
-        for (int i = threadIdx.x; i < n_words; i += 256) meta_dst[i] = c.w[i];
         zero_page[threadIdx.x] = 0u;     // kZeroBytes = 256 * 4
+        const TableLayout lay = table_layout(in.T(), in.n_seg(), in.n_adapters(), in.n_blocks());
+        const Tables t = tables_at(meta_dst, lay);
+        if (threadIdx.x == 0) derive_phase1(in, t);
+        __threadfence_block();
+        __syncthreads();
+        derive_phase2(t, (int)threadIdx.x, 256);
+        __threadfence_block();
+        __syncthreads();
+        derive_phase3(t, (int)threadIdx.x, 256);
         return;
     }
     b -= 1;
-    const MetaHeader hdr = read_arg<MetaHeader>(c, 0);
-    const int seg_base = (int)sizeof(MetaHeader);
-    const int ad_base = seg_base + hdr.n_seg * (int)sizeof(SegInfo);
     if (b < n_pack) {
-        const AdapterInfo a = read_arg<AdapterInfo>(c, ad_base + (b / pack_bx) * (int)sizeof(AdapterInfo));
-        pack_block(a, hdr.D, b % pack_bx, at, ap, want_at, want_ap, sh.pack);
+        const int k = b / pack_bx;
+        PackJob a;
+        int64_t at_rows = 0, ap_rows = 0;
+        for (int j = 0; j < k; ++j) {
+            const int rj = in.ad_rank(j);
+            at_rows += pad_to(rj, kRankPadMfma);
+            ap_rows += pad_to(rj, kRankPadGemm);
+        }
+        const int64_t D = in.D();
+        a.A = static_cast<const uint16_t *>(in.ad_ptr(k, 0));
+        a.r = in.ad_rank(k);
+        a.rp = pad_to(a.r, kRankPadGemm);
+        a.r16 = pad_to(a.r, kRankPadMfma);
+        a.at_off = at_rows * D;
+        a.ap_off = ap_rows * D;
+        pack_block(a, D, b % pack_bx, at, ap, want_at, want_ap, static_cast<uint16_t *>(shared_mem));
         return;
     }
     b -= n_pack;
     const int blk = b / (kSkinnyRows / 16), slice = b % (kSkinnyRows / 16);
-    const int tiles = (int)((hdr.T + kGemmTileRows - 1) / kGemmTileRows);
-    const int blk_base = ad_base + hdr.n_adapters * (int)sizeof(AdapterInfo) + tiles * (int)sizeof(TileExt);
-    const int s = (int)c.w[blk_base / 4 + blk];
-    const SegInfo g = read_arg<SegInfo>(c, seg_base + s * (int)sizeof(SegInfo));
-    h_to_zt_slice(g, blk, slice, hf, zt, sh.tr);
+    // walk the segments up to the one that owns token block blk, keeping the running offsets
+    const int n_seg = in.n_seg();
+    int64_t h = 0, zto = 0;
+    int blk0 = 0, row0 = 0;
+    TransposeJob g;
+    g.len = 0; g.r = 0; g.r16 = 0; g.lp = 0; g.t_block = 0; g.h_off = 0; g.zt_off = 0;
+    for (int s = 0; s < n_seg; ++s) {
+        const int row1 = in.seg_row1(s), a = in.seg_adapter(s);
+        const int len = row1 - row0;
+        row0 = row1;
+        if (a < 0) continue;
+        const int r = in.ad_rank(a), r16 = pad_to(r, kRankPadMfma), lp = pad_to(len, kTokPad);
+        const int nb = (len + kSkinnyRows - 1) / kSkinnyRows;
+        if (blk < blk0 + nb) {
+            g.len = len; g.r = r; g.r16 = r16; g.lp = lp; g.t_block = (blk - blk0) * kSkinnyRows;
+            g.h_off = h; g.zt_off = zto;
+            break;
+        }
+        blk0 += nb;
+        h += (int64_t)len * r;
+        zto += (int64_t)r16 * lp;
+    }
+    h_to_zt_slice(g, slice, hf, zt, static_cast<float *>(shared_mem));
 }
 
-bool prep_fits(size_t blob_bytes) { return blob_bytes <= sizeof(BlobChunk); }
+union PrepShared {
+    uint16_t pack[64 * PLORA_MAX_RANK];
+    float tr[16 * PLORA_MAX_RANK];
+};
 
-hipError_t launch_prep(const MetaHeader &h, void *meta_dev, const void *blob_host, size_t blob_bytes, void *zero_dev,
-                       void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt, hipStream_t st)
+__global__ void __launch_bounds__(256) k_prep_arg(DescChunk c, char *meta_dst, uint32_t *zero_page, uint16_t *at, uint16_t *ap,
+                                                 int want_at, int want_ap, int pack_bx, int n_pack, const float *hf,
+                                                 uint16_t *zt)
 {
-    BlobChunk c;
-    std::memset(&c, 0, sizeof(c));
-    std::memcpy(c.w, blob_host, blob_bytes);
+    __shared__ __attribute__((aligned(16))) PrepShared sh;
+    const DescReader<WordsInArg> in{WordsInArg{c}};
+    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, hf, zt, &sh);
+}
+
+__global__ void __launch_bounds__(256) k_prep_mem(const uint32_t *desc, char *meta_dst, uint32_t *zero_page, uint16_t *at,
+                                                 uint16_t *ap, int want_at, int want_ap, int pack_bx, int n_pack,
+                                                 const float *hf, uint16_t *zt)
+{
+    __shared__ __attribute__((aligned(16))) PrepShared sh;
+    const DescReader<WordsInMemory> in{WordsInMemory{desc}};
+    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, hf, zt, &sh);
+}
+
+hipError_t launch_prep(const uint32_t *desc_host, int n_words, const MetaHeader &h, char *meta_dev, uint32_t *desc_stage,
+                       void *zero_dev, void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt,
+                       hipStream_t st)
+{
+    static_assert(kZeroBytes == 1024, "the zero page is written by one 256-thread workgroup");
     const bool pack = h.n_adapters > 0 && (want_at || want_ap);
     const int pack_bx = (int)((h.D + 63) / 64);
     const int n_pack = pack ? pack_bx * h.n_adapters : 0;
     const int n_tr = (hf && zt) ? h.n_blocks * (kSkinnyRows / 16) : 0;
-    hipLaunchKernelGGL(k_prep, dim3((unsigned)(1 + n_pack + n_tr)), dim3(256), 0, st, c, static_cast<uint32_t *>(meta_dev),
-                       (int)((blob_bytes + 3) / 4), static_cast<uint32_t *>(zero_dev), static_cast<uint16_t *>(at),
-                       static_cast<uint16_t *>(ap), want_at ? 1 : 0, want_ap ? 1 : 0, pack_bx > 0 ? pack_bx : 1, n_pack, hf,
-                       static_cast<uint16_t *>(zt));
+    const dim3 grid((unsigned)(1 + n_pack + n_tr));
+    if (n_words <= kChunkWords) {
+        DescChunk c;
+        std::memcpy(c.w, desc_host, (size_t)n_words * 4);
+        hipLaunchKernelGGL(k_prep_arg, grid, dim3(256), 0, st, c, meta_dev, static_cast<uint32_t *>(zero_dev),
+                           static_cast<uint16_t *>(at), static_cast<uint16_t *>(ap), want_at ? 1 : 0, want_ap ? 1 : 0,
+                           pack_bx > 0 ? pack_bx : 1, n_pack, hf, static_cast<uint16_t *>(zt));
+        return hipGetLastError();
+    }
+    hipError_t e = upload_words(desc_stage, desc_host, n_words, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_prep_mem, grid, dim3(256), 0, st, static_cast<const uint32_t *>(desc_stage), meta_dev,
+                       static_cast<uint32_t *>(zero_dev), static_cast<uint16_t *>(at), static_cast<uint16_t *>(ap),
+                       want_at ? 1 : 0, want_ap ? 1 : 0, pack_bx > 0 ? pack_bx : 1, n_pack, hf, static_cast<uint16_t *>(zt));
     return hipGetLastError();
 }
 

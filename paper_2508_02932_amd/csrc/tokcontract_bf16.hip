@@ -309,6 +309,13 @@ int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters)
     return tokc_plan(h, C, n_active_adapters, nullptr);
 }
 
+int tokc_tile_columns(const MetaHeader &h, int64_t C, int n_active_adapters)
+{
+    int bc = 256;
+    (void)tokc_plan(h, C, n_active_adapters, &bc);
+    return bc;
+}
+
 template <bool WANT_DA, int BC>
 static hipError_t launch_tokc(const MetaView &mv, const MetaHeader &h, const uint16_t *S, int C, const uint16_t *zt,
                               const uint16_t *zero, float *part, int n_split, int r16_total, hipStream_t st)
@@ -321,12 +328,10 @@ static hipError_t launch_tokc(const MetaView &mv, const MetaHeader &h, const uin
     int nst = (int)(budget / stage);
     nst = nst > TC_MAX_NST ? TC_MAX_NST : nst;
     const size_t lds = nst * stage;
-    static size_t allowed = 0;
     auto kern = k_tokc<WANT_DA, BC>;
-    if (lds > allowed) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    {
+        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(kern), 1 + (WANT_DA ? 2 : 0) + (BC == 256 ? 1 : 0));
         if (e != hipSuccess) return e;
-        allowed = lds;
     }
     const dim3 grid((unsigned)((C + BC - 1) / BC), (unsigned)h.n_adapters, (unsigned)n_split);
     hipLaunchKernelGGL(kern, grid, dim3(2 * BC), lds, st, mv, S, C, zt, zero, n_split > 1 ? part : nullptr, r16_total, nst);

@@ -20,11 +20,11 @@ LIB_PATH = os.path.join(_HERE, "libplora.so")
 PLORA_BF16, PLORA_F32 = 0, 1
 PLORA_OK = 0
 PLORA_MAX_RANK, PLORA_MAX_ADAPTERS, PLORA_MAX_SEGMENTS = 128, 256, 1024
-KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "pack": 6, "convert": 7}
+KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "prep": 6}
 
 EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_workspace_bytes",
            "plora_build_metadata", "plora_linear_fwd", "plora_linear_fwd_noalloc", "plora_linear_bwd",
-           "plora_set_kernel_timing", "plora_kernel_time"]
+           "plora_set_kernel_timing", "plora_kernel_time", "plora_debug_metadata"]
 
 
 class PloraError(RuntimeError):
@@ -39,6 +39,29 @@ class plora_desc(C.Structure):
                 ("seg_off", C.c_void_p), ("seg_adapter", C.c_void_p),
                 ("rank", C.c_void_p), ("scale", C.c_void_p), ("dtype", C.c_int32)]
 
+
+class plora_debug_info(C.Structure):
+    _fields_ = ([("n_tiles", C.c_int64)]
+                + [(n, C.c_int32) for n in ("n_seg", "n_adapters", "n_blocks", "max_r16", "seg_stride", "ad_stride",
+                                            "tile_stride", "desc_words")]
+                + [(n, C.c_uint64) for n in ("off_hdr", "off_seg", "off_ad", "off_tile", "off_blk_seg", "off_seg_list",
+                                             "table_bytes")]
+                + [(n, C.c_int32) for n in ("shrink_splits", "dh_splits", "da_splits", "da_tile_cols", "db_splits",
+                                            "db_tile_cols", "r16_total", "n_active")]
+                + [(n, C.c_uint64) for n in ("ws_zero", "ws_meta", "ws_desc", "ws_at", "ws_ap", "ws_hb", "ws_zt_h",
+                                             "ws_zt_g", "ws_hf", "ws_gf", "ws_part", "ws_wpart", "ws_total", "h_elems")])
+
+
+# numpy views of the records of the table image (include/plora_debug.h)
+SEG_DTYPE = np.dtype([(n, "<i4") for n in ("row0", "row1", "adapter", "r", "rp", "r16", "blk0", "lp")]
+                     + [(n, "<i8") for n in ("h_off", "hb_off", "zt_off")])
+AD_DTYPE = np.dtype([(n, "<u8") for n in ("A", "B", "dA", "dB")] + [("r", "<i4"), ("rp", "<i4"), ("r16", "<i4"),
+                    ("scale", "<f4"), ("at_off", "<i8"), ("ap_off", "<i8")]
+                    + [(n, "<i4") for n in ("r16_off", "by_tokens", "seg_list0", "n_own", "tokens", "reserved")])
+_GSEG = [("row0", "<i4"), ("row1", "<i4"), ("rp", "<i4"), ("r", "<i4"), ("hb_off", "<i8"), ("B", "<u8"), ("ap_off", "<i8")]
+TILE_DTYPE = np.dtype([(n, "<i4") for n in ("n_ext", "n_own", "first_seg", "third_seg")]
+                      + [("s", np.dtype(_GSEG), (2,))])
+HDR_DTYPE = np.dtype([("T", "<i8"), ("D", "<i8"), ("K", "<i8")] + [(n, "<i4") for n in ("n_seg", "n_adapters", "n_blocks", "max_r16")])
 
 _lib = None
 
@@ -70,6 +93,8 @@ def lib():
         L.plora_set_kernel_timing.argtypes = [C.c_int]
         L.plora_kernel_time.restype = C.c_int
         L.plora_kernel_time.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
+        L.plora_debug_metadata.restype = C.c_int
+        L.plora_debug_metadata.argtypes = [C.POINTER(plora_desc), C.POINTER(plora_debug_info), C.c_void_p, C.c_size_t]
         _lib = L
     return _lib
 
@@ -132,6 +157,34 @@ def plora_build_metadata(d: Desc, block_rows: int):
     n2 = int(lib().plora_build_metadata(d.ref, block_rows, h_off.ctypes.data, blocks.ctypes.data, n))
     assert n2 == n
     return h_off, blocks[:n]
+
+
+def parse_tables(info: plora_debug_info, image: np.ndarray) -> dict:
+    """Splits a table image (uint8 array, as exported or as read back from the workspace) into its records."""
+    assert info.seg_stride == SEG_DTYPE.itemsize and info.ad_stride == AD_DTYPE.itemsize
+    assert info.tile_stride == TILE_DTYPE.itemsize
+    buf = np.ascontiguousarray(image, dtype=np.uint8)
+
+    def take(off, dtype, n):
+        return np.frombuffer(buf, dtype=dtype, count=n, offset=int(off)).copy()
+
+    tabs = {"hdr": take(info.off_hdr, HDR_DTYPE, 1)[0], "seg": take(info.off_seg, SEG_DTYPE, info.n_seg),
+            "ad": take(info.off_ad, AD_DTYPE, info.n_adapters), "tile": take(info.off_tile, TILE_DTYPE, info.n_tiles),
+            "blk_seg": take(info.off_blk_seg, "<i4", info.n_blocks)}
+    n_list = int(tabs["ad"]["n_own"].sum()) if info.n_adapters else 0
+    tabs["seg_list"] = take(info.off_seg_list, "<i4", n_list)
+    return tabs
+
+
+def plora_debug_metadata(d: Desc):
+    """(info, tables) - the metadata exactly as the kernels read it, built on the host (no device)."""
+    info = plora_debug_info()
+    if lib().plora_debug_metadata(d.ref, C.byref(info), None, 0) != 0:
+        raise PloraError(-1, "invalid description")
+    image = np.zeros(int(info.table_bytes), dtype=np.uint8)
+    if lib().plora_debug_metadata(d.ref, C.byref(info), image.ctypes.data, image.nbytes) != 0:
+        raise PloraError(-1, "plora_debug_metadata failed")
+    return info, parse_tables(info, image), image
 
 
 def _ptr(t) -> Optional[int]:

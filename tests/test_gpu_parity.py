@@ -242,3 +242,53 @@ def test_side_stream_and_workspace_reuse():
         got = [gh.to_np(dp.y), gh.to_np(dp.dx)] + [gh.to_np(a) for a in dp.dA] + [gh.to_np(b) for b in dp.dB]
         for a, b in zip(got, ref[name]):
             assert np.array_equal(a, b), name
+
+
+def _device_tables_equal_export(lin):
+    """The tables the preparation kernel derived in the workspace are, byte for byte, the ones the host
+    exports (and the brute-force tests check), adapter pointers aside."""
+    import torch
+    import gpu_harness as gh
+    from paper_2508_02932_amd import plora
+    t = lin.tensors()
+    dp = gh.upload(lin, t)
+    gh.forward(dp)
+    gh.backward(dp)
+    torch.cuda.synchronize()
+    gh.check_guards(dp)
+    info, tabs, image = plora.plora_debug_metadata(dp.desc)
+    dev = dp.ws[info.ws_meta:info.ws_meta + info.table_bytes].cpu().numpy()
+    got = plora.parse_tables(info, dev)
+    for k in range(lin.layout.n_adapters):      # the device copy carries this call's pointers
+        assert int(got["ad"][k]["A"]) == dp.A[k].data_ptr() and int(got["ad"][k]["dB"]) == dp.dB[k].data_ptr()
+    for name in ("A", "B", "dA", "dB"):
+        got["ad"][name] = 0
+    got["tile"]["s"]["B"] = 0
+    assert got["hdr"] == tabs["hdr"]
+    for name in ("seg", "ad", "tile", "blk_seg", "seg_list"):
+        assert np.array_equal(got[name], tabs[name]), name
+    return dp
+
+
+def test_device_tables_equal_host_export():
+    lin = wl.small("tables_dev", "bf16", 328, 264, lengths=[130, 0, 257, 64, 249, 1, 700, 30, 12],
+                   seg_adapter=[1, 0, 2, -1, 1, 0, 3, 2, 0], ranks=[8, 24, 72, 128], scales=[2.0, 0.5, 1.25, 1.0], seed=151)
+    _device_tables_equal_export(lin)
+
+
+def test_many_adapters_chunked_description():
+    """More adapters than one kernel argument carries (the description is uploaded in chunks first):
+    same tables, same results."""
+    n_ad = 100
+    rng = np.random.default_rng(9)
+    lengths = rng.integers(0, 40, size=120).tolist()
+    seg_adapter = rng.integers(-1, n_ad, size=120).tolist()
+    ranks = rng.integers(1, 33, size=n_ad).tolist()
+    lin = wl.small("many_adapters", "bf16", 136, 264, lengths=lengths, seg_adapter=seg_adapter, ranks=ranks,
+                   scales=[1.0] * n_ad, seed=157)
+    from paper_2508_02932_amd import plora
+    import gpu_harness as gh
+    info, _, _ = plora.plora_debug_metadata(gh.desc_of(lin))
+    assert info.desc_words > 896
+    _device_tables_equal_export(lin)
+    run_and_compare(lin)
