@@ -2,15 +2,26 @@
 """Benchmark of the packed multi-LoRA linear layer (forward + backward) on one MI355X.
 
 A "step" is one pass of the whole hot path over one batch of synthetic input: plora_linear_fwd
-followed by plora_linear_bwd on the Llama-3-8B-shaped q_proj configuration (d_in = d_out = 4096,
-bf16, 4 adapters of rank 8/16/32/64 with 2048 tokens each), inputs resident in HBM.
+followed by plora_linear_bwd, inputs resident in HBM.  The headline workload is the largest
+single-GPU configuration: the 70B-shaped MLP up projection (configuration 5, second linear:
+d_in = 8192, d_out = 28672, 32768 tokens, 32 adapters of rank 8..128 in unequal segments).
 
-Prints ONE JSON line: whole-step TFLOP/s (FLOPs = 4 T D K + 6 (D+K) sum(L r)), tokens/s, the
-roofline of the dominant kernel (the forward base GEMM with the fused expand, timed with HIP events
-on its own stream inside a second pass of the same steps), the other kernels' rates, and the fp64
-CPU oracle timed on a bounded sample of the same workload.
+Prints ONE JSON line:
+  value / tokens_per_s  whole-step rate of the headline workload; FLOPs = 4 T D K + 6 (D+K) sum(L r)
+  roofline              the dominant kernel (forward base GEMM with the fused expand): algorithmic FLOPs /
+                        average launch duration, HIP events on the call's own stream (library timing hook)
+  kernels               every kernel class the same way: GEMMs against the bf16 MFMA peak, the streaming
+                        kernels (shrink, dH, dB, dA) as algorithmic bytes / time against the HBM peak; both
+                        also as a fraction of the ceilings measured in this run (plain streaming read,
+                        MFMA-only loop)
+  per_config            the other configurations: 2, 3 (both linears), 4 (seven linears of a decoder layer,
+                        forward in order then backward in reverse on one stream, with the total), 5 (attention)
+  cpu_baseline          the fp64 oracle on a bounded sample of the headline workload, on the host cores
+Inputs of a step rotate over enough distinct sets of x / dy (more than 512 MB of them) that no kernel
+finds its input in the 256 MB last-level cache from the step before.
 """
 import argparse
+import ctypes as C
 import json
 import os
 import sys
@@ -23,19 +34,21 @@ for p in (ROOT, os.path.join(ROOT, "tests")):
 
 PEAK_BF16_MFMA_TFLOPS = 2500.0     # MI355X dense bf16 matrix peak
 PEAK_HBM_GBS = 8000.0              # MI355X HBM3E peak
+ROTATE_BYTES = 600 << 20           # distinct input bytes a kernel sees before a buffer comes round again
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--config", type=int, default=2, help="workload configuration 1..5 (default: the headline one)")
-    ap.add_argument("--linear", type=int, default=0, help="which linear of the configuration")
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5 (default: the headline one)")
+    ap.add_argument("--linear", type=int, default=1, help="which linear of the configuration")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--no-per-config", action="store_true", help="skip the per_config array (profiling runs)")
+    ap.add_argument("--no-context", action="store_true", help="skip the ceilings and the vendor-GEMM context figures")
     ap.add_argument("--sequential", action="store_true",
-                    help="also time the same step issued one adapter per call (context figure; off by default so "
-                         "that a profile of the default command only holds the packed kernels)")
+                    help="also time the same step issued one adapter per call (context figure)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 256 MiB device copy a few times (reference for the rocprofv3 "
                          "FETCH_SIZE / WRITE_SIZE counters when profiling this script)")
@@ -55,19 +68,143 @@ def main():
     torch.cuda.set_device(0)
     plora.lib()
 
+    # ---- measured ceilings (bench-side library, not the product) -----------------------------------
+    ceil = {"stream_read_gbs": None, "mfma_only_tflops": None, "mfma_only_constant_operands_tflops": None}
+    if not args.no_context:
+        blib_path = os.path.join(ROOT, "paper_2508_02932_amd", "libplora_bench.so")
+        if os.path.exists(blib_path):
+            bl = C.CDLL(blib_path)
+            buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+            sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+            v = C.c_double(0)
+            st = int(torch.cuda.current_stream().cuda_stream) or None
+            if bl.plora_bench_stream_read(C.c_void_p(buf.data_ptr()), C.c_size_t(buf.numel()), 5,
+                                          C.c_void_p(sink.data_ptr()), C.c_void_p(st), C.byref(v)) == 0:
+                ceil["stream_read_gbs"] = round(v.value, 1)
+            if bl.plora_bench_mfma_only(C.c_void_p(sink.data_ptr()), C.c_float(40.0), 1, C.c_void_p(st), C.byref(v)) == 0:
+                ceil["mfma_only_tflops"] = round(v.value, 1)        # random operands: the ceiling for real data
+            if bl.plora_bench_mfma_only(C.c_void_p(sink.data_ptr()), C.c_float(40.0), 0, C.c_void_p(st), C.byref(v)) == 0:
+                ceil["mfma_only_constant_operands_tflops"] = round(v.value, 1)
+            del buf, sink
+            torch.cuda.empty_cache()
+
+    def gpu_tensors(lin, seed):
+        """Synthetic inputs of a linear drawn on the device (same distributions as workloads.py)."""
+        lay = lin.layout
+        g = torch.Generator(device="cuda").manual_seed(seed)
+        dt = torch.bfloat16
+        D, K, T = lin.D, lin.K, lay.T
+        x = torch.randn(T, D, device="cuda", generator=g).to(dt)
+        W = (torch.randn(D, K, device="cuda", generator=g) * (1.0 / D ** 0.5)).to(dt)
+        dy = torch.randn(T, K, device="cuda", generator=g).to(dt)
+        A = [((torch.rand(D, int(r), device="cuda", generator=g) * 2 - 1) * (1.0 / D ** 0.5)).to(dt) for r in lay.rank]
+        B = [(torch.randn(int(r), K, device="cuda", generator=g) * (lin.var_B ** 0.5)).to(dt) for r in lay.rank]
+        return x, W, dy, A, B
+
+    class Runner:
+        """One linear on the device with rotating input sets; step(i) = forward + backward."""
+
+        def __init__(self, lin, tensors=None, seed=0):
+            self.lin = lin
+            lay = lin.layout
+            self.desc = gh.desc_of(lin)
+            if tensors is None:
+                x, W, dy, A, B = gpu_tensors(lin, seed)
+            else:
+                x, W, dy = (gh.to_dev(tensors.x, lin.dtype), gh.to_dev(tensors.W, lin.dtype), gh.to_dev(tensors.dy, lin.dtype))
+                A = [gh.to_dev(a, lin.dtype) for a in tensors.A]
+                B = [gh.to_dev(b, lin.dtype) for b in tensors.B]
+            T, D, K = lay.T, lin.D, lin.K
+            e = x.element_size()
+            self.n_sets = max(1, -(-ROTATE_BYTES // max(min(T * D, T * K) * e, 1)))
+            self.xs = [x] + [x.clone() for _ in range(self.n_sets - 1)]
+            self.dys = [dy] + [dy.clone() for _ in range(self.n_sets - 1)]
+            self.W, self.A, self.B = W, A, B
+            self.y = torch.empty(T, K, dtype=x.dtype, device="cuda")
+            self.dx = torch.empty(T, D, dtype=x.dtype, device="cuda")
+            self.h = torch.empty(max(plora.plora_h_elems(self.desc), 1), dtype=torch.float32, device="cuda")
+            self.dA = [torch.empty(D, int(r), dtype=torch.float32, device="cuda") for r in lay.rank]
+            self.dB = [torch.empty(int(r), K, dtype=torch.float32, device="cuda") for r in lay.rank]
+            self.ws = torch.empty(plora.plora_workspace_bytes(self.desc), dtype=torch.uint8, device="cuda")
+
+        def fwd(self, i):
+            plora.plora_linear_fwd(self.desc, self.xs[i % self.n_sets], self.W, self.A, self.B, self.y, self.h, self.ws)
+
+        def bwd(self, i):
+            plora.plora_linear_bwd(self.desc, self.xs[i % self.n_sets], self.W, self.A, self.B, self.dys[i % self.n_sets],
+                                   self.h, self.dx, self.dA, self.dB, self.ws)
+
+        def step(self, i):
+            self.fwd(i)
+            self.bwd(i)
+
+    def work_of(lin):
+        lay = lin.layout
+        T, D, K = lay.T, lin.D, lin.K
+        e = 2 if lin.dtype == "bf16" else 4
+        sum_Lr = lay.sum_Lr()
+        R = int(sum(int(r) for r in lay.rank))
+        return {
+            "gemm_fwd": ("mfma", 2.0 * T * D * K + 2.0 * K * sum_Lr),
+            "gemm_dx": ("mfma", 2.0 * T * D * K + 2.0 * D * sum_Lr),
+            "shrink": ("hbm", T * D * e + D * R * e + sum_Lr * 4.0),
+            "dh": ("hbm", T * K * e + R * K * e + sum_Lr * 4.0),
+            "db": ("hbm", T * K * e + sum_Lr * 4.0 + R * K * 4.0),
+            "da": ("hbm", T * D * e + sum_Lr * 4.0 + D * R * 4.0),
+        }
+
+    def kernel_table(lin, kern_ms):
+        out = {}
+        for name, (bound, work) in work_of(lin).items():
+            ms = kern_ms.get(name)
+            if not ms:
+                continue
+            if bound == "mfma":
+                a = work / (ms * 1e-3) / 1e12
+                ent = {"ms": round(ms, 4), "bound": bound, "achieved": round(a, 1), "unit": "TFLOP/s",
+                       "frac": round(a / PEAK_BF16_MFMA_TFLOPS, 4)}
+                if ceil["mfma_only_tflops"]:
+                    ent["frac_of_measured_ceiling"] = round(a / ceil["mfma_only_tflops"], 4)
+            else:
+                a = work / (ms * 1e-3) / 1e9
+                ent = {"ms": round(ms, 4), "bound": bound, "achieved": round(a, 1), "unit": "GB/s",
+                       "frac": round(a / PEAK_HBM_GBS, 4), "algorithmic_bytes": int(work)}
+                if ceil["stream_read_gbs"]:
+                    ent["frac_of_measured_ceiling"] = round(a / ceil["stream_read_gbs"], 4)
+            out[name] = ent
+        if kern_ms.get("prep"):
+            out["prep"] = {"ms": round(kern_ms["prep"], 4)}
+        return out
+
+    def timed(step_fn, steps, warmup):
+        for i in range(warmup):
+            step_fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step_fn(warmup + i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    def kernel_times(step_fn, steps):
+        plora.plora_set_kernel_timing(True)
+        for i in range(steps):
+            step_fn(i)
+        torch.cuda.synchronize()
+        kern = {}
+        for name in plora.KERNEL_CLASSES:
+            ms, n = plora.plora_kernel_time(name)
+            kern[name] = (ms / n) if n else None
+        plora.plora_set_kernel_timing(False)
+        return kern
+
+    # ---- headline workload ---------------------------------------------------------------------
     lin = wl.config(args.config)[args.linear]
     lay = lin.layout
     T, D, K = lay.T, lin.D, lin.K
-    e = 2 if lin.dtype == "bf16" else 4
     t = lin.tensors()
-    dp = gh.upload(lin, t)
-    sum_Lr = lay.sum_Lr()
-    R = int(sum(int(r) for r in lay.rank))
+    run = Runner(lin, t)
     flops = lin.flops_fwd_bwd()
-
-    def step():
-        plora.plora_linear_fwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.y, dp.h, dp.ws)
-        plora.plora_linear_bwd(dp.desc, dp.x, dp.W, dp.A, dp.B, dp.dy, dp.h, dp.dx, dp.dA, dp.dB, dp.ws)
 
     if args.calib_copy:
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
@@ -77,41 +214,55 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    ms_per_step = timed(run.step, args.steps, args.warmup)
 
     # spread of single steps (context; the metric above is the mean of the timed region): one event pair per step
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    for a, b in evs:
+    for i, (a, b) in enumerate(evs):
         a.record()
-        step()
+        run.step(i)
         b.record()
     torch.cuda.synchronize()
     per_step = sorted(a.elapsed_time(b) for a, b in evs)
     step_stats = {"median_ms": round(per_step[len(per_step) // 2], 4), "min_ms": round(per_step[0], 4),
                   "max_ms": round(per_step[-1], 4)}
 
-    # second pass of the same steps with every kernel bracketed by HIP events on its stream
-    plora.plora_set_kernel_timing(True)
-    for _ in range(args.steps):
-        step()
+    # host time of one call: the calls only enqueue, so timing them without synchronising measures the host side
     torch.cuda.synchronize()
-    kern = {}
-    for name in plora.KERNEL_CLASSES:
-        ms, n = plora.plora_kernel_time(name)
-        kern[name] = (ms / n) if n else None
-    plora.plora_set_kernel_timing(False)
+    t0 = time.perf_counter()
+    n_host = 20
+    for i in range(n_host):
+        run.fwd(i)
+    host_fwd_us = (time.perf_counter() - t0) * 1e6 / n_host
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(n_host):
+        run.bwd(i)
+    host_bwd_us = (time.perf_counter() - t0) * 1e6 / n_host
+    torch.cuda.synchronize()
 
-    # context leg (not the metric): the same work issued one adapter at a time, i.e. one forward and one
-    # backward call per adapter on its own rows with a single-segment description - the launch pattern
-    # that packing replaces (the paper's kernel tables compare against it)
+    # second pass of the same steps with every kernel bracketed by HIP events on its stream
+    kern = kernel_times(run.step, args.steps)
+    kernels = kernel_table(lin, kern)
+
+    # context: the vendor GEMM library on the same operands (not part of the metric)
+    vendor = None
+    if not args.no_context and lin.dtype == "bf16":
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        n_v = 5
+        out = {}
+        for name, a_, b_, c_ in (("fwd", run.xs[0], run.W, run.y), ("dx", run.dys[0], run.W.t(), run.dx)):
+            for _ in range(2):
+                torch.matmul(a_, b_, out=c_)
+            e0.record()
+            for _ in range(n_v):
+                torch.matmul(a_, b_, out=c_)
+            e1.record()
+            torch.cuda.synchronize()
+            out[name + "_tflops"] = round(2.0 * T * D * K / (e0.elapsed_time(e1) / n_v * 1e-3) / 1e12, 1)
+        vendor = dict(out, note="torch.matmul (hipBLASLt) on the same x, W, dy without the low-rank terms; context only")
+
+    # context leg (not the metric): the same work issued one adapter at a time
     sequential = None
     if args.sequential and lay.n_adapters > 0 and all(int(a) >= 0 for a in lay.seg_adapter) \
             and len(set(int(a) for a in lay.seg_adapter)) == lay.n_seg:
@@ -124,73 +275,102 @@ def main():
             if L == 0:
                 continue
             d = plora.Desc(L, D, K, np.array([0, L]), np.array([0]), np.array([lay.rank[k]]),
-                           np.array([lay.scale[k]]), dp.desc.dtype)
-            assert plora.plora_workspace_bytes(d) <= dp.ws.numel()
+                           np.array([lay.scale[k]]), run.desc.dtype)
+            assert plora.plora_workspace_bytes(d) <= run.ws.numel()
             n_h = L * int(lay.rank[k])
-            subs.append((d, dp.x[lo:hi], dp.y[lo:hi], dp.dy[lo:hi], dp.dx[lo:hi], [dp.A[k]], [dp.B[k]],
-                         [dp.dA[k]], [dp.dB[k]], dp.h[h_off:h_off + n_h]))
+            subs.append((d, run.xs[0][lo:hi], run.y[lo:hi], run.dys[0][lo:hi], run.dx[lo:hi], [run.A[k]], [run.B[k]],
+                         [run.dA[k]], [run.dB[k]], run.h[h_off:h_off + n_h]))
             h_off += n_h
 
-        def seq_step():
+        def seq_step(i):
             for d, x_, y_, dy_, dx_, A_, B_, dA_, dB_, h_ in subs:
-                plora.plora_linear_fwd(d, x_, dp.W, A_, B_, y_, h_, dp.ws)
+                plora.plora_linear_fwd(d, x_, run.W, A_, B_, y_, h_, run.ws)
             for d, x_, y_, dy_, dx_, A_, B_, dA_, dB_, h_ in subs:
-                plora.plora_linear_bwd(d, x_, dp.W, A_, B_, dy_, h_, dx_, dA_, dB_, dp.ws)
+                plora.plora_linear_bwd(d, x_, run.W, A_, B_, dy_, h_, dx_, dA_, dB_, run.ws)
 
-        n_seq = max(5, args.steps // 2)
-        for _ in range(3):
-            seq_step()
-        torch.cuda.synchronize()
-        t0s = time.perf_counter()
-        for _ in range(n_seq):
-            seq_step()
-        torch.cuda.synchronize()
-        seq_ms = (time.perf_counter() - t0s) * 1e3 / n_seq
+        n_seq = max(3, args.steps // 4)
+        seq_ms = timed(seq_step, n_seq, 2)
         sequential = {"ms_per_step": round(seq_ms, 4), "steps": n_seq, "calls_per_step": 2 * len(subs),
                       "packed_speedup": round(seq_ms / ms_per_step, 3),
                       "note": "same library, one forward and one backward call per adapter on its own rows"}
 
-    # algorithmic work per launch of each kernel (true ranks, nothing padded)
-    alg = {
-        "gemm_fwd": ("mfma", 2.0 * T * D * K + 2.0 * K * sum_Lr),
-        "gemm_dx": ("mfma", 2.0 * T * D * K + 2.0 * D * sum_Lr),
-        "shrink": ("hbm", T * D * e + D * R * e + sum_Lr * 4.0),
-        "dh": ("hbm", T * K * e + R * K * e + sum_Lr * 4.0),
-        "db": ("hbm", T * K * e + sum_Lr * 4.0 + R * K * 4.0),
-        "da": ("hbm", T * D * e + sum_Lr * 4.0 + D * R * 4.0),
-    }
-    kernels = {}
-    for name, (bound, work) in alg.items():
-        ms = kern.get(name)
-        if not ms:
-            continue
-        if bound == "mfma":
-            a = work / (ms * 1e-3) / 1e12
-            kernels[name] = {"ms": round(ms, 4), "bound": bound, "achieved": round(a, 1), "unit": "TFLOP/s",
-                             "frac": round(a / PEAK_BF16_MFMA_TFLOPS, 4)}
-        else:
-            a = work / (ms * 1e-3) / 1e9
-            kernels[name] = {"ms": round(ms, 4), "bound": bound, "achieved": round(a, 1), "unit": "GB/s",
-                             "frac": round(a / PEAK_HBM_GBS, 4)}
-    if kern.get("pack"):
-        kernels["pack"] = {"ms": round(kern["pack"], 4)}
-    # when the saved activation is handed to backward, class "shrink" of the last call is the
-    # conversion kernel; the forward shrink is what the roofline entry should describe
+    # ---- fabric traffic of the dominant kernel: committed rocprofv3 summary of this very workload, used only
+    # if it was taken from the kernel source as it stands now (otherwise null)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_config{args.config}_linear{args.linear}.txt")
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{lin.name}.txt")
     if os.path.exists(tpath):
-        # committed summary of two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this script, already
-        # scaled by the copy-kernel calibration; line format: "gemm_fwd <bytes per launch>"
+        import hashlib
+        src = os.path.join(ROOT, "paper_2508_02932_amd", "csrc", "gemm_bf16.hip")
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()[:16]
+        vals = {}
         for line in open(tpath):
             parts = line.split()
-            if len(parts) >= 2 and parts[0] == "gemm_fwd":
-                traffic = float(parts[1])
+            if len(parts) >= 2 and not line.startswith("#"):
+                vals[parts[0]] = parts[1]
+        if vals.get("kernel_source_sha16") == sha and "gemm_fwd" in vals:
+            traffic = float(vals["gemm_fwd"])
     dom = kernels.get("gemm_fwd", {})
     roofline = {"kernel": "k_gemm<forward> (x W with fused scale*h*B_k)", "bound": "mfma",
                 "achieved": dom.get("achieved"), "peak": PEAK_BF16_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": dom.get("frac"), "traffic": traffic,
-                "avg_launch_ms": dom.get("ms")}
+                "frac": dom.get("frac"), "traffic": traffic, "avg_launch_ms": dom.get("ms"),
+                "frac_of_measured_ceiling": dom.get("frac_of_measured_ceiling")}
+    rotation = {"input_sets": run.n_sets, "bytes_of_x_and_dy_per_set": int(T * (D + K) * 2),
+                "note": "x and dy of step i come from set i mod input_sets; the sets of one tensor total more than "
+                        f"{ROTATE_BYTES >> 20} MB"}
 
+    # ---- the other configurations -----------------------------------------------------------------
+    per_config = None
+    if not args.no_per_config:
+        headline = (args.config, args.linear)
+        del run
+        torch.cuda.empty_cache()
+        per_config = []
+        n_pc = max(4, args.steps // 2)
+        for cfg in (2, 3, 4, 5):
+            lins = wl.config(cfg)
+            entries = []
+            for li, l2 in enumerate(lins):
+                if (cfg, li) == headline:
+                    continue
+                if cfg == 5 and li == 1:
+                    continue                      # the 28672-wide linear is the default headline; skip unless chosen
+                r2 = Runner(l2, None, seed=1000 * cfg + li)
+                ms2 = timed(r2.step, n_pc, 3)
+                k2 = kernel_times(r2.step, n_pc)
+                f2 = l2.flops_fwd_bwd()
+                entries.append((l2, r2, {"workload": f"config {cfg} / {l2.name}: d_in={l2.D} d_out={l2.K} T={l2.layout.T} "
+                                                     f"adapters={l2.layout.n_adapters}",
+                                         "ms_per_step": round(ms2, 4), "tflops": round(f2 / (ms2 * 1e-3) / 1e12, 1),
+                                         "tokens_per_s": round(l2.layout.T / (ms2 * 1e-3), 1), "input_sets": r2.n_sets,
+                                         "kernels": kernel_table(l2, k2)}))
+                if cfg != 4:
+                    del r2
+                    entries[-1] = (l2, None, entries[-1][2])
+                    torch.cuda.empty_cache()
+            if cfg == 4:
+                runs = [r for _, r, _ in entries]
+
+                def layer_step(i):
+                    for r in runs:
+                        r.fwd(i)
+                    for r in reversed(runs):
+                        r.bwd(i)
+
+                ms4 = timed(layer_step, n_pc, 3)
+                f4 = sum(l.flops_fwd_bwd() for l, _, _ in entries)
+                per_config.append({"workload": "config 4: the seven linears of a decoder layer (q,k,v,o,gate,up,down), forward "
+                                               "in order then backward in reverse, one stream",
+                                   "ms_per_step": round(ms4, 4), "tflops": round(f4 / (ms4 * 1e-3) / 1e12, 1),
+                                   "tokens_per_s": round(entries[0][0].layout.T / (ms4 * 1e-3), 1),
+                                   "linears": [e for _, _, e in entries]})
+                del runs
+                for i in range(len(entries)):
+                    entries[i] = (entries[i][0], None, entries[i][2])
+                torch.cuda.empty_cache()
+            else:
+                per_config += [e for _, _, e in entries]
+
+    # ---- CPU baseline: the oracle on a bounded sample of the headline workload -------------------------
     cpu = None
     if not args.no_cpu:
         import oracle
@@ -198,6 +378,7 @@ def main():
         p = make_problem(oracle, lin, t)
         rng = np.random.default_rng(0)
         cores = oracle.loops.threads()
+        sum_Lr = lay.sum_Lr()
 
         def rows_time(n):
             rows = np.sort(rng.choice(T, size=min(n, T), replace=False))
@@ -207,7 +388,7 @@ def main():
             return time.perf_counter() - a, len(rows)
 
         probe_s, probe_n = rows_time(2 * cores)
-        n_rows = int(max(2 * cores, min(T, 12.0 / max(probe_s / probe_n, 1e-6))))
+        n_rows = int(max(2 * cores, min(T, 10.0 / max(probe_s / probe_n, 1e-6))))
         rows_s, n_rows = rows_time(n_rows)
         # weight gradients: every adapter when that stays within a few seconds, else the largest-rank one
         k_big = int(np.argmax(lay.rank))
@@ -217,7 +398,7 @@ def main():
         oracle.loops.grad_adapter(p, t.dy, k_big)
         one_s = time.perf_counter() - a
         done = [k_big]
-        if one_s * (sum_Lr / max(Lr[k_big], 1)) < 15.0:
+        if one_s * (sum_Lr / max(Lr[k_big], 1)) < 12.0:
             for k in range(lay.n_adapters):
                 if k != k_big and Lr[k] > 0:
                     oracle.loops.grad_adapter(p, t.dy, k)
@@ -231,7 +412,8 @@ def main():
                "tokens_per_s": round(T / est_step_s, 2),
                "sample": f"fp64 scalar-loop oracle: y and dx of {n_rows} random rows of {T} ({rows_s:.1f} s) plus "
                          f"dA, dB of {len(done)} of {lay.n_adapters} adapters ({grad_s:.1f} s); "
-                         + ("the whole step, nothing extrapolated" if whole else "whole step extrapolated")}
+                         + ("the whole step, nothing extrapolated" if whole else
+                            "whole step extrapolated: row part scaled by T / rows, weight gradients by sum(L r)")}
 
     out = {
         "metric": "packed multi-LoRA layer fwd+bwd TFLOP/s",
@@ -241,6 +423,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "step_ms": step_stats,
+        "host_us_per_call": {"fwd": round(host_fwd_us, 1), "bwd": round(host_bwd_us, 1)},
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if lin.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config} / {lin.name}: d_in={D} d_out={K} T={T} "
@@ -250,7 +433,11 @@ def main():
         "frac_of_bf16_mfma_peak": round(flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),
         "roofline": roofline,
         "kernels": kernels,
+        "measured_ceilings": ceil,
+        "rotation": rotation,
+        "vendor_gemm": vendor,
         "sequential_adapters": sequential,
+        "per_config": per_config,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

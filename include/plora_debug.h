@@ -31,8 +31,7 @@
  *              2 x { int32 row0, row1, rp, r; int64 hb_off; ptr B; int64 ap_off } }
  *            n_own = segments with an adapter and at least one row that overlap the tile,
  *            first_seg / third_seg = the first / third of them (n_seg if there is none), the two
- *            records describe the first two; n_ext = the largest sum of rp / 64 over such
- *            segments among the tiles of the same group of 4 consecutive tiles
+ *            records describe the first two; n_ext = the sum of rp / 64 over such segments
  *   blk_seg[n_blocks] int32: segment of each 128-row token block
  *   seg_list int32: the non-empty segments with an adapter, grouped by adapter, in segment order
  */

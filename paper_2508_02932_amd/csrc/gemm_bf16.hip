@@ -187,14 +187,13 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
     int n_it = 0;
     // cursor over the extension steps: ext_pos = which of the tile's segments is being issued (0 and 1 are spelled
     // out in the tile's record, from 2 on the segment table is walked: ext_walk = index of that segment), ext_kk =
-    // its next rank column, ext_left = segments not finished yet.  The record is re-read where it is used - it sits
+    // its next rank column.  The record is re-read where it is used - it sits
     // in the scalar cache by then - rather than held in registers, which this kernel has none to spare of.
-    int ext_pos = 0, ext_left = 0, ext_kk = 0, ext_walk = 0;
+    int ext_pos = 0, ext_kk = 0, ext_walk = 0;
     const int n_seg_all = n_seg;
     auto scan_segments = [&]() {
         const GemmTile *gt = mv.tile + __builtin_amdgcn_readfirstlane(m0 / BM);
         n_it = nk_main + gt->n_ext;
-        ext_left = gt->n_own;
         ext_walk = gt->third_seg;
         ext_pos = 0;
         ext_kk = 0;
@@ -206,7 +205,6 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
     };
     auto ext_advance = [&]() {
         ext_kk = 0;
-        ext_left -= 1;
         if (ext_pos >= 2) ext_walk = next_ext_seg(mv, n_seg_all, ext_walk + 1, m1);   // rare: over two segments in a row tile
         ext_pos += 1;
     };
@@ -248,10 +246,6 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
                     load_ptr(ok ? static_cast<const void *>(gw + off_w[jj]) : zero, dst + jj * 4096);
                 }
             }
-        } else if (ext_left <= 0) {
-            // padding step (the tile's own segments are used up): zeros
-#pragma unroll
-            for (int jj = 0; jj < NL; ++jj) load_ptr(zero, dst + jj * 4096);
         } else {
             const int kk = __builtin_amdgcn_readfirstlane(ext_kk);
             const GemmSeg es = ext_segment();
@@ -289,9 +283,6 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
                     load_ptr(ok ? static_cast<const void *>(gx + off_x[jj]) : zero, dst + jj * 4096);
                 }
             }
-        } else if (ext_left <= 0) {
-#pragma unroll
-            for (int jj = 0; jj < NL; ++jj) load_ptr(zero, dst + jj * 4096);
         } else {
             const int kk = __builtin_amdgcn_readfirstlane(ext_kk);
             const GemmSeg es = ext_segment();

@@ -98,7 +98,6 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     const DescReader<WordsInMemory> in{WordsInMemory{words.data()}};
     derive_phase1(in, m.t);
     derive_phase2(m.t, 0, 1);
-    derive_phase3(m.t, 0, 1);
     m.hdr = *m.t.hdr;
 
     int64_t h = 0, hb = 0, zt = 0, at = 0, ap = 0;

@@ -25,7 +25,7 @@ constexpr int kGemmGroupRows = 4;   // row tiles that the GEMM's tile order keep
 //
 // The host validates the description and ships it to the device in a compact form (a few 32-bit
 // words per segment and adapter, passed by value as a kernel argument).  The tables the kernels
-// read are derived from it by one set of routines (derive_phase1..3) compiled for both sides: the
+// read are derived from it by one set of routines (derive_phase1, derive_phase2) compiled for both sides: the
 // device runs them inside the preparation kernel and writes the tables into the workspace; the
 // host runs the very same code to size the workspace, to plan the launches and to export the
 // tables for the brute-force tests.
@@ -84,9 +84,7 @@ struct GemmSeg {
 // overlaps the tile.  The first two such segments are spelled out, so that a tile gets all it needs
 // with one fetch, issued a whole tile ahead.
 struct GemmTile {
-    int32_t n_ext;        // extension steps the tile runs: the largest own count among the row tiles of its group of
-                          // kGemmGroupRows (steps beyond the tile's own segments multiply zeros), so that the workgroups
-                          // of an XCD stay in step along the contraction and keep hitting each other's lines in its L2
+    int32_t n_ext;        // extension steps of the tile: sum of rp / 64 over the segments counted in n_own
     int32_t n_own;        // segments with an adapter and rows that overlap the tile
     int32_t first_seg;    // the first of them (n_seg if none)
     int32_t third_seg;    // the third of them (n_seg if fewer): where the walk over the segment table resumes
@@ -197,9 +195,9 @@ PLORA_HD MetaView view_of(const Tables &t)
     return v;
 }
 
-// ---- derivation of the tables, in three phases ----------------------------------------------------
-// Phase 1 runs on one thread (prefix sums over adapters and segments); phases 2 and 3 are loops
-// "for (i = tid; i < n; i += nthreads)" over independent entries.  A phase reads what the phases before it wrote, so
+// ---- derivation of the tables, in two phases ------------------------------------------------------
+// Phase 1 runs on one thread (prefix sums over adapters and segments); phase 2 is loops
+// "for (i = tid; i < n; i += nthreads)" over independent entries.  Phase 2 reads what phase 1 wrote, so
 // the caller separates them with a barrier (device: one workgroup, __syncthreads; host: tid 0 of 1, nothing to do).
 
 template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, const Tables &t)
@@ -278,7 +276,7 @@ PLORA_HD int seg_of_block(const SegInfo *seg, int n_seg, int blk)
     return lo;
 }
 
-// Own extension steps and the first segments of one GEMM row tile (n_ext is left at the own count).
+// Extension steps and the first segments of one GEMM row tile.
 PLORA_HD void derive_tile(const Tables &t, int n_seg, int64_t T, int64_t tile)
 {
     const int64_t m0 = tile * kGemmTileRows;
@@ -328,19 +326,6 @@ PLORA_HD void derive_phase2(const Tables &t, int tid, int nthreads)
             if (theirs > mine || (theirs == mine && j < k)) ++rank;
         }
         t.ad[rank].by_tokens = k;
-    }
-}
-
-PLORA_HD void derive_phase3(const Tables &t, int tid, int nthreads)
-{
-    // equal step counts inside a group of row tiles; one thread per group, so nobody reads a count already raised
-    const int64_t n_tiles = (t.hdr->T + kGemmTileRows - 1) / kGemmTileRows;
-    const int64_t n_groups = (n_tiles + kGemmGroupRows - 1) / kGemmGroupRows;
-    for (int64_t grp = tid; grp < n_groups; grp += nthreads) {
-        const int64_t t0 = grp * kGemmGroupRows, t1 = t0 + kGemmGroupRows < n_tiles ? t0 + kGemmGroupRows : n_tiles;
-        int32_t mx = 0;
-        for (int64_t q = t0; q < t1; ++q) mx = t.tile[q].n_ext > mx ? t.tile[q].n_ext : mx;
-        for (int64_t q = t0; q < t1; ++q) t.tile[q].n_ext = mx;
     }
 }
 

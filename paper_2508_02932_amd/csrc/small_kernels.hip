@@ -167,9 +167,6 @@ __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint
         __threadfence_block();
         __syncthreads();
         derive_phase2(t, (int)threadIdx.x, 256);
-        __threadfence_block();
-        __syncthreads();
-        derive_phase3(t, (int)threadIdx.x, 256);
         return;
     }
     b -= 1;

@@ -54,9 +54,8 @@ def brute_force(T, D, seg_off, seg_adapter, rank):
             if seg_adapter[s] >= 0 and s not in segs:
                 segs.append(s)
         tiles.append(dict(segs=segs, own_ext=sum(seg[s]["rp"] // 64 for s in segs)))
-    for i, tl in enumerate(tiles):
-        g0 = i // 4 * 4
-        tl["n_ext"] = max(q["own_ext"] for q in tiles[g0:g0 + 4])
+    for tl in tiles:
+        tl["n_ext"] = tl["own_ext"]
     return seg, ad, by_tokens, seg_list, blk_seg, tiles, h, max([pad(rank[seg_adapter[s]], 16) for s in range(n_seg)
                                                                  if seg_adapter[s] >= 0 and seg_off[s + 1] > seg_off[s]] + [0])
 
@@ -132,8 +131,7 @@ def test_tables_equal_brute_force_random_layouts(seed):
 
 
 def test_tables_many_blocks_and_tiny_segments():
-    """More than 256 token blocks; several segments inside one 256-row tile (the third_seg walk); tiles
-    whose group neighbours raise their step count."""
+    """More than 256 token blocks; several segments inside one 256-row tile (the third_seg walk)."""
     lens = [40000, 3, 5, 7, 60, 1, 255, 256, 257, 0, 130]
     seg_off = np.concatenate([[0], np.cumsum(lens)]).tolist()
     seg_adapter = [0, 1, 2, -1, 3, 1, 0, 2, 2, 3, -1]
