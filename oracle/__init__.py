@@ -8,8 +8,11 @@ cases of appendix C.2), both computing in fp64:
 * ``matmul`` - the same formulas with numpy's fp64 matrix product as the step, fast enough for
   whole tensors of the larger configurations.
 
+``adamw`` holds the per-adapter optimizer step that follows the backward pass (fp64, element by
+element).
+
 Nothing here imports, or is imported by, the HIP library or its binding.  Only the tests, the
 smoke check and the benchmark's ``cpu_baseline`` leg may use this package.
 """
 from .problem import Problem  # noqa: F401
-from . import loops, matmul  # noqa: F401
+from . import adamw, loops, matmul  # noqa: F401
