@@ -162,6 +162,42 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
                               float *const *dB, void *workspace, size_t ws_bytes,
                               void *hip_stream);
 
+/*
+ * Per-adapter optimizer step after a backward call (section 2.4: every adapter keeps its own
+ * parameters and optimizer state; appendix B: AdamW with gradient, momentum and velocity per
+ * adapter; Table 1: the learning rate is a per-job hyperparameter).  AdamW as published, in the
+ * order the common frameworks apply it, for every element of A_k and B_k of every adapter k:
+ *     theta <- theta (1 - lr_k wd_k);  m <- beta1_k m + (1 - beta1_k) g;  v <- beta2_k v + (1 - beta2_k) g^2
+ *     theta <- theta - lr_k (m / (1 - beta1_k^t_k)) / (sqrt(v / (1 - beta2_k^t_k)) + eps_k)
+ * fp32 arithmetic.  The parameter proper is the fp32 master copy; the copy in the layer's I/O type
+ * (what plora_linear_fwd / _bwd read) is rewritten from it, bf16 rounded to nearest even.
+ */
+typedef struct {
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t step;                 /* t of this update: 1 for the adapter's first step                */
+} plora_adamw_hparams;
+
+/* One side (all A_k, or all B_k): HOST arrays of n_adapters DEVICE pointers, 16-byte aligned,
+ * each tensor in the shape of A_k ([d_in][r_k]) or B_k ([r_k][d_out]). */
+typedef struct {
+    void *const *param;           /* desc->dtype copy, overwritten.  NULL table: no copy is kept     */
+    float *const *master;         /* fp32 parameters, updated in place.  NULL table: only for
+                                     PLORA_F32, then param itself is the parameter                   */
+    const float *const *grad;     /* fp32 gradients as written by plora_linear_bwd                   */
+    float *const *m;              /* fp32 first moment, updated in place                             */
+    float *const *v;              /* fp32 second moment, updated in place                            */
+} plora_adamw_side;
+
+/*
+ * Enqueues the update of every adapter on the stream (one or two launches per 40 tensors; no
+ * workspace).  Only T-independent parts of desc are used: d_in, d_out, n_adapters, rank, dtype
+ * (the description is validated as a whole).  hp: HOST array of n_adapters.  Errors as for the
+ * other calls: PLORA_ERR_NULL for a missing table or pointer (param and master both absent, master
+ * absent with bf16), PLORA_ERR_ALIGN, PLORA_ERR_SHAPE for step < 1 or betas outside [0, 1).
+ */
+plora_status plora_adamw_step(const plora_desc *desc, const plora_adamw_side *A, const plora_adamw_side *B,
+                              const plora_adamw_hparams *hp, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

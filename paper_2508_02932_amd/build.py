@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libplora.so")
 BENCH_LIB = os.path.join(HERE, "libplora_bench.so")      # ceiling microkernels for bench.py, not the product
 SOURCES = ["plora_api.hip", "small_kernels.hip", "f32_kernels.hip", "skinny_bf16.hip",
-           "gemm_bf16.hip", "tokcontract_bf16.hip"]
+           "gemm_bf16.hip", "tokcontract_bf16.hip", "adamw.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -34,7 +34,7 @@ def _compile(src: str) -> str:
 def build(verbose: bool = False) -> str:
     """Compile every HIP source and link the shared library.  Always recompiles."""
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=7) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(_compile, SOURCES + ["bench_ceilings.hip"]))
     for lib, parts in ((LIB, objs[:-1]), (BENCH_LIB, objs[-1:])):
         cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *parts]

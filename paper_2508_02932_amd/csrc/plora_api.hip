@@ -551,6 +551,50 @@ plora_status plora_linear_fwd_noalloc(const plora_desc *desc, const void *x, con
     )
 }
 
+static plora_status adamw_collect(const plora_desc *d, const plora_adamw_side *s, bool is_A, const plora_adamw_hparams *hp,
+                                  std::vector<AdamwTensor> &out)
+{
+    if (!s || !s->grad || !s->m || !s->v) return PLORA_ERR_NULL;
+    if (!s->param && !s->master) return PLORA_ERR_NULL;
+    if (!s->master && d->dtype != PLORA_F32) return PLORA_ERR_NULL;
+    for (int32_t k = 0; k < d->n_adapters; ++k) {
+        AdamwTensor t;
+        t.param = s->param ? s->param[k] : nullptr;
+        t.master = s->master ? s->master[k] : nullptr;
+        t.grad = s->grad[k]; t.m = s->m[k]; t.v = s->v[k];
+        if (!t.grad || !t.m || !t.v || (s->param && !t.param) || (s->master && !t.master)) return PLORA_ERR_NULL;
+        if (misaligned(t.param) || misaligned(t.master) || misaligned(t.grad) || misaligned(t.m) || misaligned(t.v))
+            return PLORA_ERR_ALIGN;
+        t.numel = (uint64_t)d->rank[k] * (uint64_t)(is_A ? d->d_in : d->d_out);
+        t.lr = hp[k].lr; t.beta1 = hp[k].beta1; t.beta2 = hp[k].beta2; t.eps = hp[k].eps;
+        t.weight_decay = hp[k].weight_decay; t.step = hp[k].step;
+        out.push_back(t);
+    }
+    return PLORA_OK;
+}
+
+plora_status plora_adamw_step(const plora_desc *desc, const plora_adamw_side *A, const plora_adamw_side *B,
+                              const plora_adamw_hparams *hp, void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        const plora_status v = validate(desc);
+        if (v != PLORA_OK) return v;
+        if (desc->n_adapters == 0) return PLORA_OK;
+        if (!hp) return PLORA_ERR_NULL;
+        for (int32_t k = 0; k < desc->n_adapters; ++k)
+            if (hp[k].step < 1 || !(hp[k].beta1 >= 0.f && hp[k].beta1 < 1.f) || !(hp[k].beta2 >= 0.f && hp[k].beta2 < 1.f))
+                return PLORA_ERR_SHAPE;
+        std::vector<AdamwTensor> jobs;
+        jobs.reserve(2 * (size_t)desc->n_adapters);
+        plora_status ps = adamw_collect(desc, A, true, hp, jobs);
+        if (ps != PLORA_OK) return ps;
+        ps = adamw_collect(desc, B, false, hp, jobs);
+        if (ps != PLORA_OK) return ps;
+        PL_TRY(launch_adamw(jobs.data(), (int)jobs.size(), desc->dtype == PLORA_BF16, static_cast<hipStream_t>(hip_stream)));
+        return PLORA_OK;
+    )
+}
+
 plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void *W,
                               const void *const *A, const void *const *B, const void *dy,
                               const float *h_saved, void *dx, float *const *dA, float *const *dB,

@@ -384,4 +384,14 @@ hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward
 hipError_t launch_f32_wgrad(const MetaView &mv, const MetaHeader &h, bool want_dA, const float *S, int64_t C,
                             const float *side, hipStream_t st);
 
+// optimizer ----------------------------------------------------------------------------------------
+struct AdamwTensor {
+    void *param; float *master; const float *grad; float *m, *v;
+    uint64_t numel;
+    float lr, beta1, beta2, eps, weight_decay;
+    int32_t step;
+};
+// AdamW step of n tensors (any sizes, each with its own hyperparameters); bf16 tells the type of `param`.
+hipError_t launch_adamw(const AdamwTensor *t, int n, bool bf16, hipStream_t st);
+
 }  // namespace plora

@@ -24,7 +24,7 @@ KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "d
 
 EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_workspace_bytes",
            "plora_build_metadata", "plora_linear_fwd", "plora_linear_fwd_noalloc", "plora_linear_bwd",
-           "plora_set_kernel_timing", "plora_kernel_time", "plora_debug_metadata"]
+           "plora_set_kernel_timing", "plora_kernel_time", "plora_debug_metadata", "plora_adamw_step"]
 
 
 class PloraError(RuntimeError):
@@ -38,6 +38,15 @@ class plora_desc(C.Structure):
                 ("n_seg", C.c_int32), ("n_adapters", C.c_int32),
                 ("seg_off", C.c_void_p), ("seg_adapter", C.c_void_p),
                 ("rank", C.c_void_p), ("scale", C.c_void_p), ("dtype", C.c_int32)]
+
+
+class plora_adamw_hparams(C.Structure):
+    _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
+                ("weight_decay", C.c_float), ("step", C.c_int32)]
+
+
+class plora_adamw_side(C.Structure):
+    _fields_ = [("param", C.c_void_p), ("master", C.c_void_p), ("grad", C.c_void_p), ("m", C.c_void_p), ("v", C.c_void_p)]
 
 
 class plora_debug_info(C.Structure):
@@ -93,6 +102,9 @@ def lib():
         L.plora_set_kernel_timing.argtypes = [C.c_int]
         L.plora_kernel_time.restype = C.c_int
         L.plora_kernel_time.argtypes = [C.c_int, C.POINTER(C.c_float), C.POINTER(C.c_int)]
+        L.plora_adamw_step.restype = C.c_int
+        L.plora_adamw_step.argtypes = [C.POINTER(plora_desc), C.POINTER(plora_adamw_side), C.POINTER(plora_adamw_side),
+                                       C.POINTER(plora_adamw_hparams), C.c_void_p]
         L.plora_debug_metadata.restype = C.c_int
         L.plora_debug_metadata.argtypes = [C.POINTER(plora_desc), C.POINTER(plora_debug_info), C.c_void_p, C.c_size_t]
         _lib = L
@@ -237,6 +249,25 @@ def plora_linear_bwd(d: Desc, x, W, A: Sequence, B: Sequence, dy, h_saved, dx, d
                                   pda, pdb, _ptr(workspace),
                                   workspace.numel() * workspace.element_size(), _stream(stream))
     _check(code)
+
+
+def plora_adamw_step(d: Desc, A_side: dict, B_side: dict, hparams: Sequence, stream=None) -> None:
+    """Enqueues the per-adapter AdamW step.  A_side / B_side: dicts with the keys param, master, grad, m, v, each a
+    list of n_adapters device tensors (param or master may be None); hparams: one (lr, beta1, beta2, eps,
+    weight_decay, step) tuple per adapter."""
+    keep = []
+
+    def side(s):
+        tabs = []
+        for key in ("param", "master", "grad", "m", "v"):
+            arr, ptr = _ptr_table(s.get(key))
+            keep.append(arr)
+            tabs.append(ptr)
+        return plora_adamw_side(*tabs)
+
+    sa, sb = side(A_side), side(B_side)
+    hp = (plora_adamw_hparams * max(len(hparams), 1))(*[plora_adamw_hparams(*h) for h in hparams])
+    _check(lib().plora_adamw_step(d.ref, C.byref(sa), C.byref(sb), hp, _stream(stream)))
 
 
 def plora_set_kernel_timing(enabled: bool) -> None:
