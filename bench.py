@@ -43,7 +43,9 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=5, help="workload configuration 1..5 (default: the headline one)")
-    ap.add_argument("--linear", type=int, default=1, help="which linear of the configuration")
+    ap.add_argument("--linear", type=int, default=1,
+                    help="which linear of the configuration; -1 with --config 4: the seven linears in sequence "
+                         "(profiling runs; prints a short JSON line of its own)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-per-config", action="store_true", help="skip the per_config array (profiling runs)")
     ap.add_argument("--no-context", action="store_true", help="skip the ceilings and the vendor-GEMM context figures")
@@ -197,6 +199,24 @@ def main():
             kern[name] = (ms / n) if n else None
         plora.plora_set_kernel_timing(False)
         return kern
+
+    if args.linear < 0:
+        # profiling mode: the linears of the configuration back to back, forward in order, backward in reverse
+        lins = wl.config(args.config)
+        runs = [Runner(l, None, seed=1000 * args.config + i) for i, l in enumerate(lins)]
+
+        def layer_step(i):
+            for r in runs:
+                r.fwd(i)
+            for r in reversed(runs):
+                r.bwd(i)
+
+        ms = timed(layer_step, args.steps, args.warmup)
+        fl = sum(l.flops_fwd_bwd() for l in lins)
+        print(json.dumps({"metric": "packed multi-LoRA layer fwd+bwd TFLOP/s", "value": round(fl / (ms * 1e-3) / 1e12, 2),
+                          "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+                          "config": {"workload": f"config {args.config}: all {len(lins)} linears in sequence"}}))
+        return
 
     # ---- headline workload ---------------------------------------------------------------------
     lin = wl.config(args.config)[args.linear]

@@ -154,7 +154,10 @@ __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, co
     for (int st = 0; st < n_st; ++st) {
         const int ahead = (n_st - 1 - st < SK_NST - 2) ? n_st - 1 - st : SK_NST - 2;
         wait_vmcnt_dyn(ahead * lps);             // this wave's loads of stage st have landed ...
-        __builtin_amdgcn_s_barrier();            // ... and everyone else's; ring slot (st-1) is free
+        __builtin_amdgcn_s_waitcnt(0xc07f);      // ... its LDS reads of the slot about to be refilled are done ...
+        __builtin_amdgcn_sched_barrier(0);       // (nothing may be moved across the barrier)
+        __builtin_amdgcn_s_barrier();            // ... and so are everyone else's; ring slot (st-1) is free
+        __builtin_amdgcn_sched_barrier(0);
         if (st + SK_NST - 1 < n_st) issue(st + SK_NST - 1);
         const char *sb = lds + (st % SK_NST) * stage_bytes;
 #pragma unroll

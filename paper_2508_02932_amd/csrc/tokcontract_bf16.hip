@@ -202,7 +202,10 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
     for (int it = 0; it < n_steps; ++it) {
         const int ahead = (n_steps - 1 - it < nst - 2) ? n_steps - 1 - it : nst - 2;
         tc_wait_vmcnt(ahead * lps);
+        __builtin_amdgcn_s_waitcnt(0xc07f);      // this wave's LDS reads of the slot about to be refilled are done
+        __builtin_amdgcn_sched_barrier(0);       // (nothing may be moved across the barrier)
         __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
         if (it + nst - 1 < n_steps) issue(wr_slot);
         const char *sb = lds + rd_slot * stage_bytes;
         rd_slot = (rd_slot + 1 == nst) ? 0 : rd_slot + 1;
