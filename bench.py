@@ -195,6 +195,8 @@ def main():
         torch.cuda.synchronize()
         kern = {}
         for name in plora.KERNEL_CLASSES:
+            if name == "adamw":
+                continue
             ms, n = plora.plora_kernel_time(name)
             kern[name] = (ms / n) if n else None
         plora.plora_set_kernel_timing(False)
@@ -227,12 +229,24 @@ def main():
     flops = lin.flops_fwd_bwd()
 
     if args.calib_copy:
+        # known traffic for calibrating FETCH_SIZE / WRITE_SIZE: a 256 MiB device copy, and the two 1 GiB streaming
+        # reads of the bench-side library (plain loads; direct-to-LDS loads, which is what the library's kernels use -
+        # the counters weigh the two kinds of request differently)
         src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
         for _ in range(5):
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+        blib_path = os.path.join(ROOT, "paper_2508_02932_amd", "libplora_bench.so")
+        if os.path.exists(blib_path):
+            bl = C.CDLL(blib_path)
+            buf = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+            sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+            v = C.c_double(0)
+            bl.plora_bench_stream_read(C.c_void_p(buf.data_ptr()), C.c_size_t(buf.numel()), 2, C.c_void_p(sink.data_ptr()),
+                                       C.c_void_p(int(torch.cuda.current_stream().cuda_stream) or None), C.byref(v))
+            del buf, sink
 
     ms_per_step = timed(run.step, args.steps, args.warmup)
 
@@ -276,14 +290,14 @@ def main():
         n_opt = 10
         for _ in range(2):
             plora.plora_adamw_step(run.desc, sA, sB, hps)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
-        e0.record()
+        plora.plora_set_kernel_timing(True)       # HIP events around the launches, on their stream
         for _ in range(n_opt):
             plora.plora_adamw_step(run.desc, sA, sB, hps)
-        e1.record()
         torch.cuda.synchronize()
-        ms_opt = e0.elapsed_time(e1) / n_opt
+        ms_tot, n_br = plora.plora_kernel_time("adamw")
+        plora.plora_set_kernel_timing(False)
+        ms_opt = ms_tot / max(n_br, 1)
         n_par = sum(int(r) for r in lay.rank) * (D + K)
         by = 30.0 * n_par                 # read master, g, m, v (16 B); write master, m, v (12 B) and the bf16 copy (2 B)
         a = by / (ms_opt * 1e-3) / 1e9

@@ -8,7 +8,7 @@
  * caller must have synchronised the streams first.
  * Classes: 0 base GEMM forward (with the fused expand), 1 dX GEMM (with the fused low-rank term),
  * 2 shrink, 3 dH, 4 dB, 5 dA, 6 the preparation launch (metadata, packing of A_k, conversion of a
- * saved activation).
+ * saved activation), 7 the optimizer step (all launches of one plora_adamw_step call).
  * Returns 0, or -1 on a bad argument or event error.  Process-global state, NOT thread-safe: one
  * benchmarking thread only, and no timed call may run concurrently with these two functions.
  */

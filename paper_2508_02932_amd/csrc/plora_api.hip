@@ -590,7 +590,8 @@ plora_status plora_adamw_step(const plora_desc *desc, const plora_adamw_side *A,
         if (ps != PLORA_OK) return ps;
         ps = adamw_collect(desc, B, false, hp, jobs);
         if (ps != PLORA_OK) return ps;
-        PL_TRY(launch_adamw(jobs.data(), (int)jobs.size(), desc->dtype == PLORA_BF16, static_cast<hipStream_t>(hip_stream)));
+        { Bracket b(7, static_cast<hipStream_t>(hip_stream));
+          PL_TRY(launch_adamw(jobs.data(), (int)jobs.size(), desc->dtype == PLORA_BF16, static_cast<hipStream_t>(hip_stream))); }
         return PLORA_OK;
     )
 }

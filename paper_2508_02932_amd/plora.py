@@ -20,7 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libplora.so")
 PLORA_BF16, PLORA_F32 = 0, 1
 PLORA_OK = 0
 PLORA_MAX_RANK, PLORA_MAX_ADAPTERS, PLORA_MAX_SEGMENTS = 128, 256, 1024
-KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "prep": 6}
+KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "prep": 6, "adamw": 7}
 
 EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_workspace_bytes",
            "plora_build_metadata", "plora_linear_fwd", "plora_linear_fwd_noalloc", "plora_linear_bwd",
