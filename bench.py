@@ -46,6 +46,9 @@ def main():
     ap.add_argument("--linear", type=int, default=1,
                     help="which linear of the configuration; -1 with --config 4: the seven linears in sequence "
                          "(profiling runs; prints a short JSON line of its own)")
+    ap.add_argument("--w-layout", choices=["in_out", "out_in", "both"], default="in_out",
+                    help="storage of the frozen weight for the headline run: W[d_in][d_out] (default), W[d_out][d_in], or "
+                         "both copies (forward reads [d_out][d_in], backward [d_in][d_out])")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--no-per-config", action="store_true", help="skip the per_config array (profiling runs)")
     ap.add_argument("--no-context", action="store_true", help="skip the ceilings and the vendor-GEMM context figures")
@@ -106,10 +109,13 @@ def main():
     class Runner:
         """One linear on the device with rotating input sets; step(i) = forward + backward."""
 
-        def __init__(self, lin, tensors=None, seed=0):
+        def __init__(self, lin, tensors=None, seed=0, w_layout=0):
             self.lin = lin
             lay = lin.layout
-            self.desc = gh.desc_of(lin)
+            # w_layout 2: the frozen weight is kept in both layouts and each direction gets the one whose contraction
+            # index is contiguous (forward [d_out][d_in], backward [d_in][d_out])
+            self.desc = gh.desc_of(lin, 1 if w_layout else 0)
+            self.desc_bwd = gh.desc_of(lin, 1 if w_layout == 1 else 0)
             if tensors is None:
                 x, W, dy, A, B = gpu_tensors(lin, seed)
             else:
@@ -121,19 +127,22 @@ def main():
             self.n_sets = max(1, -(-ROTATE_BYTES // max(min(T * D, T * K) * e, 1)))
             self.xs = [x] + [x.clone() for _ in range(self.n_sets - 1)]
             self.dys = [dy] + [dy.clone() for _ in range(self.n_sets - 1)]
-            self.W, self.A, self.B = W, A, B
+            self.W_bwd = W.t().contiguous() if w_layout == 1 else W      # [d_out][d_in] is the same matrix transposed in memory
+            self.W = W.t().contiguous() if w_layout == 2 else self.W_bwd
+            self.A, self.B = A, B
             self.y = torch.empty(T, K, dtype=x.dtype, device="cuda")
             self.dx = torch.empty(T, D, dtype=x.dtype, device="cuda")
             self.h = torch.empty(max(plora.plora_h_elems(self.desc), 1), dtype=torch.float32, device="cuda")
             self.dA = [torch.empty(D, int(r), dtype=torch.float32, device="cuda") for r in lay.rank]
             self.dB = [torch.empty(int(r), K, dtype=torch.float32, device="cuda") for r in lay.rank]
-            self.ws = torch.empty(plora.plora_workspace_bytes(self.desc), dtype=torch.uint8, device="cuda")
+            self.ws = torch.empty(max(plora.plora_workspace_bytes(self.desc), plora.plora_workspace_bytes(self.desc_bwd)),
+                                  dtype=torch.uint8, device="cuda")
 
         def fwd(self, i):
             plora.plora_linear_fwd(self.desc, self.xs[i % self.n_sets], self.W, self.A, self.B, self.y, self.h, self.ws)
 
         def bwd(self, i):
-            plora.plora_linear_bwd(self.desc, self.xs[i % self.n_sets], self.W, self.A, self.B, self.dys[i % self.n_sets],
+            plora.plora_linear_bwd(self.desc_bwd, self.xs[i % self.n_sets], self.W_bwd, self.A, self.B, self.dys[i % self.n_sets],
                                    self.h, self.dx, self.dA, self.dB, self.ws)
 
         def step(self, i):
@@ -225,7 +234,8 @@ def main():
     lay = lin.layout
     T, D, K = lay.T, lin.D, lin.K
     t = lin.tensors()
-    run = Runner(lin, t)
+    w_layout = {"in_out": 0, "out_in": 1, "both": 2}[args.w_layout]
+    run = Runner(lin, t, w_layout=w_layout)
     flops = lin.flops_fwd_bwd()
 
     if args.calib_copy:
@@ -314,7 +324,8 @@ def main():
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         n_v = 5
         out = {}
-        for name, a_, b_, c_ in (("fwd", run.xs[0], run.W, run.y), ("dx", run.dys[0], run.W.t(), run.dx)):
+        W_io = run.W_bwd.t() if w_layout == 1 else run.W_bwd        # [d_in][d_out] (a view when only the other copy exists)
+        for name, a_, b_, c_ in (("fwd", run.xs[0], W_io, run.y), ("dx", run.dys[0], W_io.t(), run.dx)):
             for _ in range(2):
                 torch.matmul(a_, b_, out=c_)
             e0.record()
@@ -327,7 +338,7 @@ def main():
 
     # context leg (not the metric): the same work issued one adapter at a time
     sequential = None
-    if args.sequential and lay.n_adapters > 0 and all(int(a) >= 0 for a in lay.seg_adapter) \
+    if args.sequential and w_layout == 0 and lay.n_adapters > 0 and all(int(a) >= 0 for a in lay.seg_adapter) \
             and len(set(int(a) for a in lay.seg_adapter)) == lay.n_seg:
         subs = []
         h_off = 0
@@ -432,6 +443,24 @@ def main():
                 torch.cuda.empty_cache()
             else:
                 per_config += [e for _, _, e in entries]
+        # the headline linear with the frozen weight stored the other way round (the forward and backward GEMMs
+        # swap forms: the one that contracts over W's contiguous index runs forward)
+        if lin.dtype == "bf16":
+            names = {0: "[d_in][d_out]", 1: "[d_out][d_in]",
+                     2: "in both layouts (frozen, so one extra copy in HBM buys each direction the GEMM form that "
+                        "contracts over W's contiguous index)"}
+            for other in (0, 1, 2):
+                if other == w_layout:
+                    continue
+                r3 = Runner(lin, t, w_layout=other)
+                ms3 = timed(r3.step, n_pc, 3)
+                k3 = kernel_times(r3.step, n_pc)
+                per_config.append({"workload": f"config {args.config} / {lin.name} with W stored " + names[other],
+                                   "ms_per_step": round(ms3, 4), "tflops": round(flops / (ms3 * 1e-3) / 1e12, 1),
+                                   "tokens_per_s": round(T / (ms3 * 1e-3), 1), "input_sets": r3.n_sets,
+                                   "kernels": kernel_table(lin, k3)})
+                del r3
+                torch.cuda.empty_cache()
 
     # ---- CPU baseline: the oracle on a bounded sample of the headline workload -------------------------
     cpu = None
@@ -490,7 +519,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if lin.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"config {args.config} / {lin.name}: d_in={D} d_out={K} T={T} "
-                               f"adapters={lay.n_adapters} ranks={sorted(set(int(r) for r in lay.rank))}",
+                               f"adapters={lay.n_adapters} ranks={sorted(set(int(r) for r in lay.rank))}"
+                               + ("", " W stored [d_out][d_in]", " W stored in both layouts")[w_layout],
                    "tokens": T, "d_in": D, "d_out": K, "n_adapters": lay.n_adapters,
                    "flops_per_step": flops},
         "frac_of_bf16_mfma_peak": round(flops / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_MFMA_TFLOPS, 4),

@@ -18,6 +18,9 @@
  * General conventions
  *   - All matrices are dense row-major: x[T][d_in], W[d_in][d_out], A_k[d_in][r_k],
  *     B_k[r_k][d_out], y/dy[T][d_out], dx[T][d_in], dA_k[d_in][r_k], dB_k[r_k][d_out].
+ *     With desc->w_layout = PLORA_W_OUT_IN the frozen weight alone is stored the other way round,
+ *     W[d_out][d_in] (the layout of a framework's linear module: y = x W^T); everything else keeps
+ *     the layouts above and every result is the same.
  *   - Pointers marked DEVICE point to memory of the current HIP device; pointers marked HOST are
  *     ordinary host memory that is read before the call returns (it may be freed afterwards).
  *   - The caller owns every buffer.  The library allocates no device memory; temporary storage
@@ -61,12 +64,18 @@ typedef enum {
     PLORA_ERR_RANK = 5,         /* rank outside [1, PLORA_MAX_RANK]                             */
     PLORA_ERR_ALIGN = 6,        /* a device pointer is not 16-byte aligned                      */
     PLORA_ERR_WORKSPACE = 7,    /* workspace NULL or smaller than plora_workspace_bytes()       */
-    PLORA_ERR_UNSUPPORTED = 8,  /* unknown dtype                                                */
+    PLORA_ERR_UNSUPPORTED = 8,  /* unknown dtype or weight layout                               */
     PLORA_ERR_HIP = 9,          /* a HIP call failed (launch error)                             */
     PLORA_ERR_INTERNAL = 10     /* host memory allocation failed or another internal error      */
 } plora_status;
 
 typedef enum { PLORA_BF16 = 0, PLORA_F32 = 1 } plora_dtype;
+
+/* Storage of the frozen weight. */
+typedef enum {
+    PLORA_W_IN_OUT = 0,         /* W[d_in][d_out]: rows are input features                         */
+    PLORA_W_OUT_IN = 1          /* W[d_out][d_in]: rows are output features (y = x W^T)            */
+} plora_w_layout;
 
 /* Shape and packing of one call.  Every array here is HOST memory. */
 typedef struct {
@@ -80,6 +89,7 @@ typedef struct {
     const int32_t *rank;          /* [n_adapters] r_k in [1, PLORA_MAX_RANK]                    */
     const float *scale;           /* [n_adapters] scale_k                                       */
     int32_t dtype;                /* plora_dtype of x, W, A, B, y, dy, dx                       */
+    int32_t w_layout;             /* plora_w_layout of W                                        */
 } plora_desc;
 
 /* Text for a status code (static storage, never NULL). */
@@ -118,7 +128,7 @@ int64_t plora_build_metadata(const plora_desc *desc, int32_t block_rows, int64_t
 /*
  * Forward (section 2.4; y_t = x_t W + scale_k (x_t A_k) B_k).
  *   x        DEVICE [T][d_in]
- *   W        DEVICE [d_in][d_out]
+ *   W        DEVICE [d_in][d_out], or [d_out][d_in] with PLORA_W_OUT_IN
  *   A, B     HOST arrays of n_adapters DEVICE pointers, A[k] -> [d_in][r_k], B[k] -> [r_k][d_out]
  *   y        DEVICE [T][d_out], overwritten
  *   h_saved  DEVICE fp32 [plora_h_elems] or NULL; if given it receives x_t A_k for every

@@ -11,7 +11,9 @@
  * fields aside: the export is built without adapter pointers, they read as zero).
  *
  * Image layout (little endian, offsets in plora_debug_info):
- *   header   { int64 T, D, K; int32 n_seg, n_adapters, n_blocks, max_r16 }
+ *   header   { int64 T, D, K; int32 n_seg, n_adapters, n_blocks, max_r16, w_out_in, reserved;
+ *              ptr at_base }   w_out_in = 1 when W is stored [d_out][d_in]; at_base = device address
+ *              of the packed A_k^T buffer (zero in the export)
  *   seg[n_seg], seg_stride bytes each:
  *            { int32 row0, row1, adapter, r, rp, r16, blk0, lp; int64 h_off, hb_off, zt_off }
  *            rp = rank padded to 64, r16 = rank padded to 16, lp = length padded to 64, blk0 =
@@ -21,9 +23,11 @@
  *            factors [r16][lp]
  *   ad[n_adapters], ad_stride bytes each:
  *            { ptr A, B, dA, dB; int32 r, rp, r16; float scale; int64 at_off, ap_off;
- *              int32 r16_off, by_tokens, seg_list0, n_own, tokens, reserved }
+ *              int32 r16_off, by_tokens, seg_list0, n_own, tokens, reserved; ptr ext_b }
  *            at_off / ap_off = element offsets of A_k^T [r16][d_in] and of A_k padded
- *            [d_in][rp]; r16_off = sum of r16 of the adapters before; entry i's by_tokens = the
+ *            [d_in][rp] (W stored [d_out][d_in]: of B_k^T padded [d_out][rp]); ext_b = the
+ *            [r][N] low-rank operand of the GEMM that reads W with the contraction index as row
+ *            index: B, or at_base + 2 at_off when W is stored [d_out][d_in]; r16_off = sum of r16 of the adapters before; entry i's by_tokens = the
  *            adapter with the i-th most tokens (ties: lower index first); seg_list0 / n_own =
  *            this adapter's slice of seg_list
  *   tile[n_tiles], tile_stride bytes each, one per 256 token rows:

@@ -61,7 +61,8 @@ hipError_t launch_f32_lowrank(const MetaView &mv, const MetaHeader &h, int mode,
 // forward : C[t][n] = sum_i x[t][i]  W[i][n] + scale_k sum_j h[t][j] B_k[j][n]
 // backward: C[t][i] = sum_n dy[t][n] W[i][n] +         sum_j g[t][j] A_k[i][j]     (g carries scale_k)
 // 64x64 output tile per block, 4x4 outputs per thread, contraction staged through LDS 16 at a time.
-template <bool FWD>
+// WK: the contraction index is W's row index (forward with W [d_in][d_out], backward with W [d_out][d_in]).
+template <bool FWD, bool WK>
 __global__ void __launch_bounds__(256) k_f32_gemm(MetaView mv, const float *S, const float *W, const float *side, float *Cout)
 {
     __shared__ float sA[16][64 + 1];   // [kk][row]
@@ -69,7 +70,7 @@ __global__ void __launch_bounds__(256) k_f32_gemm(MetaView mv, const float *S, c
     const int64_t T = mv.hdr->T;
     const int64_t Kd = FWD ? mv.hdr->D : mv.hdr->K;   // contraction length
     const int64_t N = FWD ? mv.hdr->K : mv.hdr->D;    // output columns
-    const int64_t ldw = mv.hdr->K;                    // W is [D][K]
+    const int64_t ldw = WK ? N : Kd;                  // W is [Kd][N] or [N][Kd]
     const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
     const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
     double acc[4][4];
@@ -83,10 +84,10 @@ __global__ void __launch_bounds__(256) k_f32_gemm(MetaView mv, const float *S, c
         }
         for (int e = threadIdx.x; e < 16 * 64; e += 256) {
             int kk, cc;
-            if (FWD) { cc = e % 64; kk = e / 64; } else { kk = e % 16; cc = e / 16; }
+            if (WK) { cc = e % 64; kk = e / 64; } else { kk = e % 16; cc = e / 16; }
             const int64_t k = k0 + kk, n = n0 + cc;
             float v = 0.f;
-            if (k < Kd && n < N) v = FWD ? W[k * ldw + n] : W[n * ldw + k];
+            if (k < Kd && n < N) v = WK ? W[k * ldw + n] : W[n * ldw + k];
             sB[kk][cc] = v;
         }
         __syncthreads();
@@ -134,8 +135,11 @@ hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward
     if (h.T == 0) return hipSuccess;
     const int64_t N = forward ? h.K : h.D;
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)((h.T + 63) / 64));
-    if (forward) hipLaunchKernelGGL(k_f32_gemm<true>, grid, dim3(256), 0, st, mv, S, W, side, C);
-    else hipLaunchKernelGGL(k_f32_gemm<false>, grid, dim3(256), 0, st, mv, S, W, side, C);
+    const bool wk = forward != (h.w_out_in != 0);
+    if (forward && wk) hipLaunchKernelGGL((k_f32_gemm<true, true>), grid, dim3(256), 0, st, mv, S, W, side, C);
+    else if (forward) hipLaunchKernelGGL((k_f32_gemm<true, false>), grid, dim3(256), 0, st, mv, S, W, side, C);
+    else if (wk) hipLaunchKernelGGL((k_f32_gemm<false, true>), grid, dim3(256), 0, st, mv, S, W, side, C);
+    else hipLaunchKernelGGL((k_f32_gemm<false, false>), grid, dim3(256), 0, st, mv, S, W, side, C);
     return hipGetLastError();
 }
 

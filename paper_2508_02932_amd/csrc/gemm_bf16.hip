@@ -19,9 +19,13 @@
 // granules of 16 KB (the two row halves of the S-side tile, two halves of the W-side tile), each
 // kind in its own small ring, 160 KB of LDS in all; the two waves that share a SIMD alternate
 // between multiplying from registers and fetching (LDS -> registers, plus one granule HBM -> LDS).
-// W is [d_in][d_out] row-major in both directions: backward contracts over its contiguous index
-// and reads operands with ds_read_b128; forward contracts over its row index and reads operands
-// with the transposing LDS load (ds_read_b64_tr_b16), so no transposed copy of W is ever made.
+// W is used as it lies in memory in both directions.  With W [d_in][d_out], backward contracts over
+// its contiguous index and reads operands with ds_read_b128; forward contracts over its row index
+// and reads operands with the transposing LDS load (ds_read_b64_tr_b16), so no transposed copy of W
+// is ever made.  With W [d_out][d_in] the two forms swap roles (forward reads with ds_read_b128),
+// and so do the low-rank operands: the form with the contraction index as row index takes its
+// extension rows from GemmSeg::B ([r][N]: B_k, or the packed A_k^T), the other from the padded
+// buffer ([N][rp]: A_k, or B_k^T).
 #include "plora_internal.h"
 
 
@@ -62,7 +66,7 @@ __device__ inline GemmSeg load_ext_seg(const MetaView &mv, int s)
     const SegInfo g = mv.seg[s];
     const AdapterInfo a = mv.ad[g.adapter];
     GemmSeg q;
-    q.row0 = g.row0; q.row1 = g.row1; q.rp = g.rp; q.r = g.r; q.hb_off = g.hb_off; q.B = a.B; q.ap_off = a.ap_off;
+    q.row0 = g.row0; q.row1 = g.row1; q.rp = g.rp; q.r = g.r; q.hb_off = g.hb_off; q.B = a.ext_b; q.ap_off = a.ap_off;
     return q;
 }
 
@@ -96,17 +100,17 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
                                               const AdapterInfo *__restrict__ ads, const uint16_t *__restrict__ S,
                                               const uint16_t *__restrict__ W, const uint16_t *__restrict__ side,
                                               const uint16_t *__restrict__ ap, const uint16_t *__restrict__ zero,
-                                              uint16_t *__restrict__ Cout, int tiles_m, int tiles_n, int M, int d_in, int d_out, int n_seg)
+                                              uint16_t *__restrict__ Cout, int tiles_m, int tiles_n, int M, int Kd, int N, int n_seg)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     // the metadata pointers come one by one and restrict-qualified: that lets the compiler fetch the records through
     // the scalar cache (a vector load would be counted, in order, with the direct-to-LDS loads of the ring)
     MetaView mv;
     mv.hdr = nullptr; mv.seg = segs; mv.ad = ads; mv.tile = tiles; mv.blk_seg = nullptr; mv.seg_list = nullptr;
-    // shapes come as kernel arguments, so the first loads do not wait for a metadata fetch
-    const int Kd = FWD ? d_in : d_out;
-    const int N = FWD ? d_out : d_in;
-    const int ldw = d_out;
+    // shapes come as kernel arguments, so the first loads do not wait for a metadata fetch.  FWD names the form of
+    // the weight operand: W[Kd][N] (contraction index = row index; the forward product when W is [d_in][d_out]),
+    // otherwise W[N][Kd]
+    const int ldw = FWD ? N : Kd;
 
     // ---- workgroup -> tiles.  The grid is persistent (one workgroup per compute unit, each walks the
     // tile ids b, b + grid, b + 2 grid, ...).  Workgroups are dealt round-robin to the 8 XCDs (each with
@@ -521,10 +525,9 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
 }
 
 template <bool FWD>
-static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, const void *S, const void *W,
+static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, int64_t Kd, int64_t N, const void *S, const void *W,
                                  const void *side, const void *ap, const void *zero, void *C, hipStream_t st)
 {
-    const int64_t N = FWD ? h.K : h.D;
     const int tiles_m = (int)((h.T + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
     auto kern = k_gemm<FWD>;
     {
@@ -539,17 +542,18 @@ static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, const 
     hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < n_cu ? n_tiles : n_cu)), dim3(512), kGemmLds, st, mv.tile, mv.seg, mv.ad,
                        static_cast<const uint16_t *>(S), static_cast<const uint16_t *>(W),
                        static_cast<const uint16_t *>(side), static_cast<const uint16_t *>(ap),
-                       static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n, (int)h.T, (int)h.D,
-                       (int)h.K, (int)h.n_seg);
+                       static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n, (int)h.T, (int)Kd,
+                       (int)N, (int)h.n_seg);
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool forward, const void *S, const void *W,
-                            const void *side, const void *ap, const void *zero, void *C, hipStream_t st)
+hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool w_rows_contract, int64_t Kd, int64_t N,
+                            const void *S, const void *W, const void *side, const void *ap, const void *zero, void *C,
+                            hipStream_t st)
 {
     if (h.T == 0) return hipSuccess;
-    if (forward) return launch_variant<true>(mv, h, S, W, side, ap, zero, C, st);
-    return launch_variant<false>(mv, h, S, W, side, ap, zero, C, st);
+    if (w_rows_contract) return launch_variant<true>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
+    return launch_variant<false>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
 }
 
 }  // namespace plora

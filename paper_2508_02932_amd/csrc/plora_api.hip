@@ -23,6 +23,7 @@ static plora_status validate(const plora_desc *d)
 {
     if (!d) return PLORA_ERR_NULL;
     if (d->dtype != PLORA_BF16 && d->dtype != PLORA_F32) return PLORA_ERR_UNSUPPORTED;
+    if (d->w_layout != PLORA_W_IN_OUT && d->w_layout != PLORA_W_OUT_IN) return PLORA_ERR_UNSUPPORTED;
     if (d->T < 0 || d->d_in <= 0 || d->d_out <= 0) return PLORA_ERR_SHAPE;
     if (d->T > INT32_MAX || d->d_in > kMaxHidden || d->d_out > kMaxHidden) return PLORA_ERR_SHAPE;
     if (d->dtype == PLORA_BF16 && (d->d_in % 8 != 0 || d->d_out % 8 != 0)) return PLORA_ERR_SHAPE;
@@ -48,12 +49,15 @@ static plora_status validate(const plora_desc *d)
 }
 
 // Compact description of a call (the words the preparation kernel receives).  Pointer tables may be null.
+// at_base: device address of the packed-A^T region of the workspace (null when only the layout matters).
 static void fill_desc_words(const plora_desc *d, int32_t n_blocks, const void *const *A, const void *const *B,
-                            float *const *dA, float *const *dB, uint32_t *w)
+                            float *const *dA, float *const *dB, const void *at_base, uint32_t *w)
 {
     auto put64 = [&](int i, uint64_t v) { w[i] = (uint32_t)v; w[i + 1] = (uint32_t)(v >> 32); };
     put64(0, (uint64_t)d->T); put64(2, (uint64_t)d->d_in); put64(4, (uint64_t)d->d_out);
-    w[6] = (uint32_t)d->n_seg; w[7] = (uint32_t)d->n_adapters; w[8] = (uint32_t)n_blocks; w[9] = 0;
+    w[6] = (uint32_t)d->n_seg; w[7] = (uint32_t)d->n_adapters; w[8] = (uint32_t)n_blocks;
+    w[9] = d->w_layout == PLORA_W_OUT_IN ? 1u : 0u;
+    put64(10, (uint64_t)(uintptr_t)at_base);
     uint32_t *p = w + kDescHeadWords;
     for (int32_t s = 0; s < d->n_seg; ++s) { *p++ = (uint32_t)d->seg_off[s + 1]; *p++ = (uint32_t)d->seg_adapter[s]; }
     for (int32_t k = 0; k < d->n_adapters; ++k) {
@@ -91,7 +95,7 @@ static void build_meta(const plora_desc *d, HostMeta &m)
         if (d->seg_adapter[s] >= 0) n_blocks += (d->seg_off[s + 1] - d->seg_off[s] + kSkinnyRows - 1) / kSkinnyRows;
     m.n_words = desc_words(d->n_seg, d->n_adapters);
     std::vector<uint32_t> words((size_t)m.n_words);
-    fill_desc_words(d, n_blocks, nullptr, nullptr, nullptr, nullptr, words.data());
+    fill_desc_words(d, n_blocks, nullptr, nullptr, nullptr, nullptr, nullptr, words.data());
     m.layout = table_layout(d->T, d->n_seg, d->n_adapters, n_blocks);
     m.image.assign(m.layout.bytes, 0);
     m.t = tables_at(m.image.data(), m.layout);
@@ -110,7 +114,8 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     m.r16_total = 0; m.n_active = 0;
     for (int32_t k = 0; k < d->n_adapters; ++k) {
         const AdapterInfo &a = m.t.ad[k];
-        at += (int64_t)a.r16 * d->d_in; ap += (int64_t)a.rp * d->d_in;
+        at += (int64_t)a.r16 * d->d_in;
+        ap += (int64_t)a.rp * (m.hdr.w_out_in ? d->d_out : d->d_in);
         m.r16_total += a.r16;
         m.n_active += a.tokens > 0;
     }
@@ -161,7 +166,7 @@ static void key_of(const plora_desc *d, std::vector<int64_t> &k)
 {
     k.clear();
     k.reserve(6 + 2 * (size_t)d->n_seg + (size_t)d->n_adapters);
-    k.push_back(d->T); k.push_back(d->d_in); k.push_back(d->d_out); k.push_back(d->dtype);
+    k.push_back(d->T); k.push_back(d->d_in); k.push_back(d->d_out); k.push_back(d->dtype + 16 * (int64_t)d->w_layout);
     k.push_back(d->n_seg); k.push_back(d->n_adapters);
     for (int32_t s = 0; s < d->n_seg; ++s) { k.push_back(d->seg_off[s + 1]); k.push_back(d->seg_adapter[s]); }
     for (int32_t a = 0; a < d->n_adapters; ++a) k.push_back(d->rank[a]);
@@ -245,7 +250,7 @@ static plora_status prepare(const plora_desc *d, const void *x, const void *W, c
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
     uint32_t *w = c.small;
     if (c.m->n_words > kChunkWords) { c.large.resize((size_t)c.m->n_words); w = c.large.data(); }
-    fill_desc_words(d, c.m->hdr.n_blocks, A, B, dA, dB, w);
+    fill_desc_words(d, c.m->hdr.n_blocks, A, B, dA, dB, static_cast<const char *>(workspace) + c.m->ws.at, w);
     c.words = w;
     return PLORA_OK;
 }
@@ -272,9 +277,10 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
     const MetaView mv = device_view(m, ws);
     const bool lora = m.hdr.n_blocks > 0;
     const bool bf = desc->dtype == PLORA_BF16;
+    const bool w_out_in = m.hdr.w_out_in != 0;
     { Bracket b(6, st);
       PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + m.ws.meta, reinterpret_cast<uint32_t *>(ws + m.ws.desc), ws + m.ws.zero,
-                         ws + m.ws.at, nullptr, bf && lora, false, nullptr, nullptr, st)); }
+                         ws + m.ws.at, ws + m.ws.ap, bf && lora, false, bf && lora && w_out_in, nullptr, nullptr, st)); }
     float *hf = h_saved ? h_saved : reinterpret_cast<float *>(ws + m.ws.hf);
 
     if (desc->dtype == PLORA_F32) {
@@ -292,7 +298,7 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
         PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, h_saved, hb, nullptr, false, st));
     }
     { Bracket b(0, st);
-      PL_TRY(launch_gemm_bf16(mv, m.hdr, true, x, W, hb, nullptr, ws + m.ws.zero, y, st)); }
+      PL_TRY(launch_gemm_bf16(mv, m.hdr, !w_out_in, desc->d_in, desc->d_out, x, W, hb, ws + m.ws.ap, ws + m.ws.zero, y, st)); }
     return PLORA_OK;
 }
 
@@ -328,9 +334,11 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
         const bool bf = desc->dtype == PLORA_BF16;
         const bool need_shrink = any_w && !h_saved;
         const bool tr = bf && lora && any_w && h_saved;
+        // the low-rank operand of the dX GEMM: padded A_k, or - W stored [d_out][d_in] - the packed A_k^T
+        const bool dx_ap = dx != nullptr && !m.hdr.w_out_in, dx_at = dx != nullptr && m.hdr.w_out_in;
         Bracket b(6, st);
         PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + m.ws.meta, reinterpret_cast<uint32_t *>(ws + m.ws.desc), ws + m.ws.zero,
-                           ws + m.ws.at, ws + m.ws.ap, bf && lora && need_shrink, bf && lora && dx != nullptr,
+                           ws + m.ws.at, ws + m.ws.ap, bf && lora && (need_shrink || dx_at), bf && lora && dx_ap, false,
                            tr ? h_saved : nullptr, tr ? ws + m.ws.zt_h : nullptr, st));
     }
 
@@ -374,7 +382,7 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
     }
     if (dx && desc->T > 0) {
         Bracket b(1, st);
-        PL_TRY(launch_gemm_bf16(mv, m.hdr, false, dy, W, gb, ap, ws + m.ws.zero, dx, st));
+        PL_TRY(launch_gemm_bf16(mv, m.hdr, m.hdr.w_out_in != 0, desc->d_out, desc->d_in, dy, W, gb, ap, ws + m.ws.zero, dx, st));
     }
     return PLORA_OK;
 }

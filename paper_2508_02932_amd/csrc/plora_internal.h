@@ -54,13 +54,15 @@ struct AdapterInfo {
     int32_t r, rp, r16;
     float scale;
     int64_t at_off;       // element offset of A^T  [r16][d_in]  in the packed-A^T buffer
-    int64_t ap_off;       // element offset of A    [d_in][rp]   in the padded-A buffer
+    int64_t ap_off;       // element offset of A    [d_in][rp]   in the padded-A buffer; with W stored [d_out][d_in]:
+                          // of B^T [d_out][rp] in that same buffer
     int32_t r16_off;      // sum of r16 over the adapters before this one (row offset in dA / dB partial tiles)
     int32_t by_tokens;    // entry i: the adapter with the i-th largest token count (ties by index)
     int32_t seg_list0;    // this adapter's non-empty segments: seg_list[seg_list0 .. seg_list0 + n_own), in segment order
     int32_t n_own;
     int32_t tokens;       // tokens of this adapter over all its segments
     int32_t reserved;
+    const void *ext_b;    // what GemmSeg::B is for this adapter's segments: B, or the packed A^T when W is [d_out][d_in]
 };
 
 struct MetaHeader {
@@ -68,6 +70,9 @@ struct MetaHeader {
     int32_t n_seg, n_adapters;
     int32_t n_blocks;     // token blocks of kSkinnyRows rows over all segments
     int32_t max_r16;      // largest rank (padded to 16) among segments with tokens
+    int32_t w_out_in;     // 1: W is stored [d_out][d_in]
+    int32_t reserved;
+    const void *at_base;  // device address of the packed-A^T buffer (only used when w_out_in)
 };
 
 // What a 256-row tile of the base GEMMs needs to know about one segment whose low-rank term it adds.
@@ -75,8 +80,10 @@ struct GemmSeg {
     int32_t row0, row1;   // rows of the segment
     int32_t rp, r;        // padded and true rank
     int64_t hb_off;       // element offset of the segment in the bf16 low-rank factor [len][rp]
-    const void *B;        // forward: B_k [r][d_out]
-    int64_t ap_off;       // backward: element offset of padded A_k [d_in][rp]
+    const void *B;        // operand of the GEMM that reads W with the contraction index as row index, [r][N]:
+                          // W[d_in][d_out]: forward, B_k;  W[d_out][d_in]: backward, the packed A_k^T
+    int64_t ap_off;       // operand of the other GEMM, [N][rp], as element offset in the padded buffer:
+                          // W[d_in][d_out]: backward, padded A_k;  W[d_out][d_in]: forward, padded B_k^T
 };
 
 // One entry per 256-row tile of the base GEMMs.  The low-rank term enters the GEMM as extra steps of
@@ -103,9 +110,9 @@ struct MetaView {
 
 // ---- compact description -----------------------------------------------------------------------
 // 32-bit words: [0,1] T  [2,3] D  [4,5] K  [6] n_seg  [7] n_adapters  [8] n_blocks (computed by the host, fixes the
-// table layout)  [9] reserved; then per segment {row1, adapter}; then per adapter {A lo, A hi, B lo, B hi, dA lo,
-// dA hi, dB lo, dB hi, r, scale bits}.
-constexpr int kDescHeadWords = 10, kDescSegWords = 2, kDescAdWords = 10;
+// table layout)  [9] 1 if W is stored [d_out][d_in]  [10,11] device address of the packed-A^T buffer; then per segment
+// {row1, adapter}; then per adapter {A lo, A hi, B lo, B hi, dA lo, dA hi, dB lo, dB hi, r, scale bits}.
+constexpr int kDescHeadWords = 12, kDescSegWords = 2, kDescAdWords = 10;
 constexpr int kChunkWords = 896;   // 3584 bytes: what one launch carries by value, below the 4 KB kernel-argument limit
 struct DescChunk { uint32_t w[kChunkWords]; };
 
@@ -128,6 +135,8 @@ template <class Src> struct DescReader {
     PLORA_HD int n_seg() const { return (int)src.word(6); }
     PLORA_HD int n_adapters() const { return (int)src.word(7); }
     PLORA_HD int n_blocks() const { return (int)src.word(8); }
+    PLORA_HD int w_out_in() const { return (int)src.word(9); }
+    PLORA_HD const void *at_base() const { return reinterpret_cast<const void *>((uintptr_t)w64(10)); }
     PLORA_HD int seg_row1(int s) const { return (int)src.word(kDescHeadWords + kDescSegWords * s); }
     PLORA_HD int seg_row0(int s) const { return s ? seg_row1(s - 1) : 0; }
     PLORA_HD int seg_adapter(int s) const { return (int)src.word(kDescHeadWords + kDescSegWords * s + 1); }
@@ -204,6 +213,7 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
 {
     const int n_seg = in.n_seg(), n_ad = in.n_adapters();
     const int64_t D = in.D();
+    const int64_t ap_rows = in.w_out_in() ? in.K() : D;   // rows of the padded operand [rows][rp], see GemmSeg
     int64_t at = 0, ap = 0;
     int32_t r16_off = 0;
     for (int k = 0; k < n_ad; ++k) {
@@ -217,7 +227,8 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
         a.r16 = pad_to(a.r, kRankPadMfma);
         a.scale = in.ad_scale(k);
         a.at_off = at; at += (int64_t)a.r16 * D;
-        a.ap_off = ap; ap += (int64_t)a.rp * D;
+        a.ext_b = in.w_out_in() ? static_cast<const void *>(static_cast<const char *>(in.at_base()) + 2 * a.at_off) : a.B;
+        a.ap_off = ap; ap += (int64_t)a.rp * ap_rows;
         a.r16_off = r16_off; r16_off += a.r16;
         a.by_tokens = 0; a.seg_list0 = 0; a.n_own = 0; a.tokens = 0; a.reserved = 0;
         t.ad[k] = a;
@@ -258,6 +269,7 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
     MetaHeader hd;
     hd.T = in.T(); hd.D = D; hd.K = in.K();
     hd.n_seg = n_seg; hd.n_adapters = n_ad; hd.n_blocks = blk; hd.max_r16 = max_r16;
+    hd.w_out_in = in.w_out_in(); hd.reserved = 0; hd.at_base = in.at_base();
     *t.hdr = hd;
 }
 
@@ -298,7 +310,7 @@ PLORA_HD void derive_tile(const Tables &t, int n_seg, int64_t T, int64_t tile)
         if (gt.n_own < 2) {
             GemmSeg &q = gt.s[gt.n_own];
             q.row0 = g.row0; q.row1 = g.row1; q.rp = g.rp; q.r = g.r; q.hb_off = g.hb_off;
-            q.B = t.ad[g.adapter].B; q.ap_off = t.ad[g.adapter].ap_off;
+            q.B = t.ad[g.adapter].ext_b; q.ap_off = t.ad[g.adapter].ap_off;
             if (gt.n_own == 0) gt.first_seg = s;
         } else if (gt.n_own == 2) {
             gt.third_seg = s;
@@ -348,9 +360,10 @@ constexpr int kLdsSlots = 16;
 // kernel argument (otherwise it is first uploaded in chunks to desc_stage): derived tables and zero page into the
 // workspace; packing of A_k (bf16 path: A_k^T [r16][d_in] with zero rows beyond r, and / or A_k padded to rp
 // columns); transposed bf16 copy of a saved activation, zt[j][t] = bf16(h[t][j]) (bf16 backward).
+// want_bp (instead of want_ap, W stored [d_out][d_in]): B_k^T [d_out][rp] with zero columns beyond r into `ap`.
 hipError_t launch_prep(const uint32_t *desc_host, int n_words, const MetaHeader &h, char *meta_dev, uint32_t *desc_stage,
-                       void *zero_dev, void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt,
-                       hipStream_t st);
+                       void *zero_dev, void *at, void *ap, bool want_at, bool want_ap, bool want_bp, const float *hf,
+                       void *zt, hipStream_t st);
 
 // bf16 path -------------------------------------------------------------------------------------
 // Skinny product over token blocks: acc[t][j] = sum_c S[t][c] * Bm_k[j][c]  (c < C).
@@ -362,10 +375,13 @@ hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode,
                               const void *at, const void *zero, float *part, float *hf, void *hb, void *zt,
                               bool zt_scaled, hipStream_t st);
 // C[T][N] = S[T][Kd] * Wop + side[T][rp] * ext_k, rounded to bf16.
-//   forward : S = x,  Wop = W [Kd=d_in][N=d_out] (contraction index is the row index), ext_k = B_k [r][N]
-//   backward: S = dy, Wop = W [N=d_in][Kd=d_out] (contraction index is contiguous),    ext_k = padded A_k [N][rp]
-hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool forward, const void *S, const void *W,
-                            const void *side, const void *ap, const void *zero, void *C, hipStream_t st);
+//   w_rows_contract : Wop = W [Kd][N] (contraction index is the row index),  ext_k = GemmSeg::B   [r][N]
+//   otherwise       : Wop = W [N][Kd] (contraction index is contiguous),     ext_k = ap + GemmSeg::ap_off [N][rp]
+//   W[d_in][d_out]: forward (S = x, Kd = d_in, N = d_out) is the first form, backward (S = dy, Kd = d_out, N = d_in)
+//   the second; W[d_out][d_in]: the other way round.
+hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool w_rows_contract, int64_t Kd, int64_t N,
+                            const void *S, const void *W, const void *side, const void *ap, const void *zero, void *C,
+                            hipStream_t st);
 // Token contraction: out_k = mult * sum_t S[t][c] * zt[j][t] over all segments of adapter k.
 //   want_dA: S = x, out = dA_k[c][j], mult = 1;  else S = dy, out = dB_k[j][c], mult = scale_k.
 //   n_split > 1: the token walk is split, partial tiles go through `part` ([split][r16_total][C] fp32).
@@ -380,7 +396,7 @@ int skinny_splits(const MetaHeader &h, int64_t C);
 hipError_t launch_f32_lowrank(const MetaView &mv, const MetaHeader &h, int mode, const float *S, int64_t C,
                               float *out, hipStream_t st);
 hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward, const float *S, const float *W,
-                           const float *side, float *C, hipStream_t st);
+                           const float *side, float *C, hipStream_t st);   // W's layout: h.w_out_in
 hipError_t launch_f32_wgrad(const MetaView &mv, const MetaHeader &h, bool want_dA, const float *S, int64_t C,
                             const float *side, hipStream_t st);
 

@@ -111,6 +111,39 @@ __device__ inline void pack_block(const PackJob &a, int64_t D, int bx, uint16_t 
     }
 }
 
+// ---- packing of B_k when W is stored [d_out][d_in] -------------------------------------------------
+// bp: B_k^T as [K][rp] with columns j >= r zero - the low-rank K-extension operand of the forward GEMM,
+//     which then reads W (and with it this operand) with the contraction index contiguous.
+// One block handles 64 columns n of one adapter: rows of B_k come in as 128-byte pieces, go through
+// LDS, and leave as whole rows of rp elements.
+struct PackBJob {
+    const uint16_t *B;
+    int r, rp;
+    int64_t bp_off;
+};
+
+__device__ inline void pack_bt_block(const PackBJob &a, int64_t K, int bx, uint16_t *bp, uint16_t *tile)
+{
+    const int64_t n0 = (int64_t)bx * 64;
+    const int cols = (int)((K - n0 < 64) ? K - n0 : 64);               // a multiple of 8
+    const int l = threadIdx.x & 7;
+    for (int j = threadIdx.x >> 3; j < a.r; j += 32) {
+        uint4 v = make_uint4(0u, 0u, 0u, 0u);
+        if (l * 8 < cols) v = *reinterpret_cast<const uint4 *>(a.B + (int64_t)j * K + n0 + l * 8);
+        reinterpret_cast<uint4 *>(tile + j * 64)[l] = v;
+    }
+    __syncthreads();
+    uint16_t *dst = bp + a.bp_off + n0 * a.rp;
+    const int vec_per_row = a.rp / 8;                                   // rp is a multiple of 64
+    for (int e = threadIdx.x; e < cols * vec_per_row; e += 256) {
+        const int nn = e / vec_per_row, v = e % vec_per_row;
+        union { uint4 q; uint16_t h[8]; } u;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) { const int j = v * 8 + t; u.h[t] = (j < a.r) ? tile[j * 64 + nn] : (uint16_t)0; }
+        reinterpret_cast<uint4 *>(dst + (int64_t)nn * a.rp)[v] = u.q;
+    }
+}
+
 // ---- transposed bf16 copy of a saved fp32 activation ------------------------------------------------
 __device__ inline uint16_t f32_to_bf16_rne(float f)
 {
@@ -145,8 +178,8 @@ __device__ inline void h_to_zt_slice(const TransposeJob &g, int slice, const flo
 
 // ---- the preparation kernel ----------------------------------------------------------------------
 // Workgroup 0 derives the metadata tables into the workspace and clears the zero page; the next
-// n_pack workgroups pack the adapter matrices; the last ones make the transposed bf16 copy of a saved
-// activation.  The packing and copy workgroups work out the few offsets they need from the compact
+// n_pack workgroups pack the A_k, the next n_pack_b the B_k (only when W is stored [d_out][d_in]); the
+// last ones make the transposed bf16 copy of a saved activation.  The packing and copy workgroups work out the few offsets they need from the compact
 // description themselves, so they do not wait for workgroup 0.
 struct WordsInArg {
     const DescChunk &c;
@@ -155,8 +188,8 @@ struct WordsInArg {
 
 template <class Src>
 __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint32_t *zero_page, uint16_t *at, uint16_t *ap,
-                                 int want_at, int want_ap, int pack_bx, int n_pack, const float *hf, uint16_t *zt,
-                                 void *shared_mem)
+                                 int want_at, int want_ap, int pack_bx, int n_pack, int pack_bx_b, int n_pack_b,
+                                 const float *hf, uint16_t *zt, void *shared_mem)
 {
     int b = blockIdx.x;
     if (b == 0) {
@@ -190,6 +223,20 @@ __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint
         return;
     }
     b -= n_pack;
+    if (b < n_pack_b) {
+        const int k = b / pack_bx_b;
+        int64_t rows = 0;
+        for (int j = 0; j < k; ++j) rows += pad_to(in.ad_rank(j), kRankPadGemm);
+        const int64_t K = in.K();
+        PackBJob a;
+        a.B = static_cast<const uint16_t *>(in.ad_ptr(k, 1));
+        a.r = in.ad_rank(k);
+        a.rp = pad_to(a.r, kRankPadGemm);
+        a.bp_off = rows * K;
+        pack_bt_block(a, K, b % pack_bx_b, ap, static_cast<uint16_t *>(shared_mem));
+        return;
+    }
+    b -= n_pack_b;
     const int blk = b / (kSkinnyRows / 16), slice = b % (kSkinnyRows / 16);
     // walk the segments up to the one that owns token block blk, keeping the running offsets
     const int n_seg = in.n_seg();
@@ -222,46 +269,51 @@ union PrepShared {
 };
 
 __global__ void __launch_bounds__(256) k_prep_arg(DescChunk c, char *meta_dst, uint32_t *zero_page, uint16_t *at, uint16_t *ap,
-                                                 int want_at, int want_ap, int pack_bx, int n_pack, const float *hf,
-                                                 uint16_t *zt)
+                                                 int want_at, int want_ap, int pack_bx, int n_pack, int pack_bx_b,
+                                                 int n_pack_b, const float *hf, uint16_t *zt)
 {
     __shared__ __attribute__((aligned(16))) PrepShared sh;
     const DescReader<WordsInArg> in{WordsInArg{c}};
-    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, hf, zt, &sh);
+    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, pack_bx_b, n_pack_b, hf, zt, &sh);
 }
 
 __global__ void __launch_bounds__(256) k_prep_mem(const uint32_t *desc, char *meta_dst, uint32_t *zero_page, uint16_t *at,
                                                  uint16_t *ap, int want_at, int want_ap, int pack_bx, int n_pack,
-                                                 const float *hf, uint16_t *zt)
+                                                 int pack_bx_b, int n_pack_b, const float *hf, uint16_t *zt)
 {
     __shared__ __attribute__((aligned(16))) PrepShared sh;
     const DescReader<WordsInMemory> in{WordsInMemory{desc}};
-    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, hf, zt, &sh);
+    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, pack_bx_b, n_pack_b, hf, zt, &sh);
 }
 
 hipError_t launch_prep(const uint32_t *desc_host, int n_words, const MetaHeader &h, char *meta_dev, uint32_t *desc_stage,
-                       void *zero_dev, void *at, void *ap, bool want_at, bool want_ap, const float *hf, void *zt,
-                       hipStream_t st)
+                       void *zero_dev, void *at, void *ap, bool want_at, bool want_ap, bool want_bp, const float *hf,
+                       void *zt, hipStream_t st)
 {
     static_assert(kZeroBytes == 1024, "the zero page is written by one 256-thread workgroup");
+    if (want_ap && want_bp) return hipErrorInvalidValue;            // both live in `ap`
     const bool pack = h.n_adapters > 0 && (want_at || want_ap);
     const int pack_bx = (int)((h.D + 63) / 64);
     const int n_pack = pack ? pack_bx * h.n_adapters : 0;
+    const int pack_bx_b = (int)((h.K + 63) / 64);
+    const int n_pack_b = (want_bp && h.n_adapters > 0) ? pack_bx_b * h.n_adapters : 0;
     const int n_tr = (hf && zt) ? h.n_blocks * (kSkinnyRows / 16) : 0;
-    const dim3 grid((unsigned)(1 + n_pack + n_tr));
+    const dim3 grid((unsigned)(1 + n_pack + n_pack_b + n_tr));
     if (n_words <= kChunkWords) {
         DescChunk c;
         std::memcpy(c.w, desc_host, (size_t)n_words * 4);
         hipLaunchKernelGGL(k_prep_arg, grid, dim3(256), 0, st, c, meta_dev, static_cast<uint32_t *>(zero_dev),
                            static_cast<uint16_t *>(at), static_cast<uint16_t *>(ap), want_at ? 1 : 0, want_ap ? 1 : 0,
-                           pack_bx > 0 ? pack_bx : 1, n_pack, hf, static_cast<uint16_t *>(zt));
+                           pack_bx > 0 ? pack_bx : 1, n_pack, pack_bx_b > 0 ? pack_bx_b : 1, n_pack_b, hf,
+                           static_cast<uint16_t *>(zt));
         return hipGetLastError();
     }
     hipError_t e = upload_words(desc_stage, desc_host, n_words, st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(k_prep_mem, grid, dim3(256), 0, st, static_cast<const uint32_t *>(desc_stage), meta_dev,
                        static_cast<uint32_t *>(zero_dev), static_cast<uint16_t *>(at), static_cast<uint16_t *>(ap),
-                       want_at ? 1 : 0, want_ap ? 1 : 0, pack_bx > 0 ? pack_bx : 1, n_pack, hf, static_cast<uint16_t *>(zt));
+                       want_at ? 1 : 0, want_ap ? 1 : 0, pack_bx > 0 ? pack_bx : 1, n_pack, pack_bx_b > 0 ? pack_bx_b : 1,
+                       n_pack_b, hf, static_cast<uint16_t *>(zt));
     return hipGetLastError();
 }
 

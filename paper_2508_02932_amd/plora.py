@@ -18,6 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libplora.so")
 
 PLORA_BF16, PLORA_F32 = 0, 1
+PLORA_W_IN_OUT, PLORA_W_OUT_IN = 0, 1
 PLORA_OK = 0
 PLORA_MAX_RANK, PLORA_MAX_ADAPTERS, PLORA_MAX_SEGMENTS = 128, 256, 1024
 KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "prep": 6, "adamw": 7}
@@ -37,7 +38,7 @@ class plora_desc(C.Structure):
     _fields_ = [("T", C.c_int64), ("d_in", C.c_int64), ("d_out", C.c_int64),
                 ("n_seg", C.c_int32), ("n_adapters", C.c_int32),
                 ("seg_off", C.c_void_p), ("seg_adapter", C.c_void_p),
-                ("rank", C.c_void_p), ("scale", C.c_void_p), ("dtype", C.c_int32)]
+                ("rank", C.c_void_p), ("scale", C.c_void_p), ("dtype", C.c_int32), ("w_layout", C.c_int32)]
 
 
 class plora_adamw_hparams(C.Structure):
@@ -66,11 +67,13 @@ SEG_DTYPE = np.dtype([(n, "<i4") for n in ("row0", "row1", "adapter", "r", "rp",
                      + [(n, "<i8") for n in ("h_off", "hb_off", "zt_off")])
 AD_DTYPE = np.dtype([(n, "<u8") for n in ("A", "B", "dA", "dB")] + [("r", "<i4"), ("rp", "<i4"), ("r16", "<i4"),
                     ("scale", "<f4"), ("at_off", "<i8"), ("ap_off", "<i8")]
-                    + [(n, "<i4") for n in ("r16_off", "by_tokens", "seg_list0", "n_own", "tokens", "reserved")])
+                    + [(n, "<i4") for n in ("r16_off", "by_tokens", "seg_list0", "n_own", "tokens", "reserved")]
+                    + [("ext_b", "<u8")])
 _GSEG = [("row0", "<i4"), ("row1", "<i4"), ("rp", "<i4"), ("r", "<i4"), ("hb_off", "<i8"), ("B", "<u8"), ("ap_off", "<i8")]
 TILE_DTYPE = np.dtype([(n, "<i4") for n in ("n_ext", "n_own", "first_seg", "third_seg")]
                       + [("s", np.dtype(_GSEG), (2,))])
-HDR_DTYPE = np.dtype([("T", "<i8"), ("D", "<i8"), ("K", "<i8")] + [(n, "<i4") for n in ("n_seg", "n_adapters", "n_blocks", "max_r16")])
+HDR_DTYPE = np.dtype([("T", "<i8"), ("D", "<i8"), ("K", "<i8")] + [(n, "<i4") for n in ("n_seg", "n_adapters", "n_blocks", "max_r16", "w_out_in", "reserved")]
+                     + [("at_base", "<u8")])
 
 _lib = None
 
@@ -122,6 +125,7 @@ class Desc:
     rank: np.ndarray
     scale: np.ndarray
     dtype: int
+    w_layout: int = 0       # PLORA_W_IN_OUT; PLORA_W_OUT_IN: W is stored [d_out][d_in]
 
     def __post_init__(self):
         self.seg_off = np.ascontiguousarray(self.seg_off, dtype=np.int32)
@@ -131,7 +135,7 @@ class Desc:
         self.c = plora_desc(self.T, self.d_in, self.d_out, len(self.seg_adapter), len(self.rank),
                             self.seg_off.ctypes.data, self.seg_adapter.ctypes.data,
                             self.rank.ctypes.data if len(self.rank) else None,
-                            self.scale.ctypes.data if len(self.scale) else None, self.dtype)
+                            self.scale.ctypes.data if len(self.scale) else None, self.dtype, self.w_layout)
 
     @property
     def ref(self):

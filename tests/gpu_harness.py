@@ -17,10 +17,10 @@ from paper_2508_02932_amd import plora
 from paper_2508_02932_amd import workloads as wl
 
 
-def desc_of(lin: wl.Linear) -> plora.Desc:
+def desc_of(lin: wl.Linear, w_layout: int = 0) -> plora.Desc:
     lay = lin.layout
     return plora.Desc(lay.T, lin.D, lin.K, lay.seg_off, lay.seg_adapter, lay.rank, lay.scale,
-                      plora.PLORA_BF16 if lin.dtype == "bf16" else plora.PLORA_F32)
+                      plora.PLORA_BF16 if lin.dtype == "bf16" else plora.PLORA_F32, w_layout)
 
 
 def to_dev(a: np.ndarray, dtype: str) -> torch.Tensor:
@@ -76,8 +76,9 @@ class DeviceProblem:
     guards: list
 
 
-def upload(lin: wl.Linear, t: wl.Tensors) -> DeviceProblem:
-    d = desc_of(lin)
+def upload(lin: wl.Linear, t: wl.Tensors, w_layout: int = 0) -> DeviceProblem:
+    """w_layout = plora.PLORA_W_OUT_IN hands the library W stored [d_out][d_in] (the same matrix, transposed in memory)."""
+    d = desc_of(lin, w_layout)
     tdt = torch.bfloat16 if lin.dtype == "bf16" else torch.float32
     ws_bytes = plora.plora_workspace_bytes(d)
     assert ws_bytes > 0
@@ -85,7 +86,7 @@ def upload(lin: wl.Linear, t: wl.Tensors) -> DeviceProblem:
     T, D, K = lin.layout.T, lin.D, lin.K
     g: list = []
     return DeviceProblem(
-        lin, d, to_dev(t.x, lin.dtype), to_dev(t.W, lin.dtype),
+        lin, d, to_dev(t.x, lin.dtype), to_dev(t.W.T if w_layout else t.W, lin.dtype),
         [to_dev(a, lin.dtype) for a in t.A], [to_dev(b, lin.dtype) for b in t.B],
         None if t.dy is None else to_dev(t.dy, lin.dtype),
         guarded((ws_bytes,), torch.uint8, None, g, "workspace"),

@@ -22,7 +22,7 @@ def say(msg):
     sys.stdout.flush()
 
 
-def run_and_compare(lin, t=None, impl=None, save_h=True, check_h=True):
+def run_and_compare(lin, t=None, impl=None, save_h=True, check_h=True, w_layout=0):
     import torch
     import gpu_harness as gh
     t = t or lin.tensors()
@@ -30,12 +30,12 @@ def run_and_compare(lin, t=None, impl=None, save_h=True, check_h=True):
     tol = TOL[lin.dtype]
     say(f"[case] {lin.name} dtype={lin.dtype} T={lin.layout.T} D={lin.D} K={lin.K} "
         f"ranks={lin.layout.rank.tolist()} segs={np.diff(lin.layout.seg_off).tolist()} "
-        f"adapters={lin.layout.seg_adapter.tolist()} save_h={save_h}")
+        f"adapters={lin.layout.seg_adapter.tolist()} save_h={save_h} w_layout={w_layout}")
     p = make_problem(oracle, lin, t)
     y_o, h_o = impl.forward(p)
     dx_o, g_o, dA_o, dB_o = impl.backward(p, t.dy)
 
-    dp = gh.upload(lin, t)
+    dp = gh.upload(lin, t, w_layout)
     say("  forward")
     gh.forward(dp, save_h=save_h)
     torch.cuda.synchronize()
@@ -244,14 +244,14 @@ def test_side_stream_and_workspace_reuse():
             assert np.array_equal(a, b), name
 
 
-def _device_tables_equal_export(lin):
+def _device_tables_equal_export(lin, w_layout=0):
     """The tables the preparation kernel derived in the workspace are, byte for byte, the ones the host
     exports (and the brute-force tests check), adapter pointers aside."""
     import torch
     import gpu_harness as gh
     from paper_2508_02932_amd import plora
     t = lin.tensors()
-    dp = gh.upload(lin, t)
+    dp = gh.upload(lin, t, w_layout)
     gh.forward(dp)
     gh.backward(dp)
     torch.cuda.synchronize()
@@ -261,9 +261,21 @@ def _device_tables_equal_export(lin):
     got = plora.parse_tables(info, dev)
     for k in range(lin.layout.n_adapters):      # the device copy carries this call's pointers
         assert int(got["ad"][k]["A"]) == dp.A[k].data_ptr() and int(got["ad"][k]["dB"]) == dp.dB[k].data_ptr()
-    for name in ("A", "B", "dA", "dB"):
+    at_base = dp.ws.data_ptr() + info.ws_at
+    assert int(got["hdr"]["at_base"]) == at_base
+    for k in range(lin.layout.n_adapters):      # the [r][N] low-rank operand: B_k, or the packed A_k^T
+        want = at_base + 2 * int(got["ad"][k]["at_off"]) if w_layout else dp.B[k].data_ptr()
+        assert int(got["ad"][k]["ext_b"]) == want
+    for rec in got["tile"]:                     # a tile's first record names the operand of its first segment's adapter
+        if int(rec["n_own"]) > 0:
+            a = int(got["seg"][int(rec["first_seg"])]["adapter"])
+            assert int(rec["s"][0]["B"]) == int(got["ad"][a]["ext_b"])
+    for name in ("A", "B", "dA", "dB", "ext_b"):
         got["ad"][name] = 0
+        tabs["ad"][name] = 0
     got["tile"]["s"]["B"] = 0
+    tabs["tile"]["s"]["B"] = 0
+    got["hdr"]["at_base"] = 0
     assert got["hdr"] == tabs["hdr"]
     for name in ("seg", "ad", "tile", "blk_seg", "seg_list"):
         assert np.array_equal(got[name], tabs[name]), name

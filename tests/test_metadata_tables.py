@@ -12,7 +12,8 @@ def pad(v, a):
     return (v + a - 1) // a * a
 
 
-def brute_force(T, D, seg_off, seg_adapter, rank):
+def brute_force(T, D, seg_off, seg_adapter, rank, ap_rows=None):
+    ap_rows = D if ap_rows is None else ap_rows     # rows of the padded [rows][rp] operand: d_in, or d_out when W is [d_out][d_in]
     n_seg, n_ad = len(seg_adapter), len(rank)
     seg = []
     h = hb = zt = blk = 0
@@ -40,7 +41,7 @@ def brute_force(T, D, seg_off, seg_adapter, rank):
         seg_list += own
         list0 += len(own)
         at += pad(rank[k], 16) * D
-        ap += pad(rank[k], 64) * D
+        ap += pad(rank[k], 64) * ap_rows
         r16_off += pad(rank[k], 16)
     by_tokens = sorted(range(n_ad), key=lambda k: (-ad[k]["tokens"], k))
     row_seg = np.full(T, -1)
@@ -60,13 +61,16 @@ def brute_force(T, D, seg_off, seg_adapter, rank):
                                                                  if seg_adapter[s] >= 0 and seg_off[s + 1] > seg_off[s]] + [0])
 
 
-def check(T, D, K, seg_off, seg_adapter, rank, scale):
-    d = plora.Desc(T, D, K, np.array(seg_off), np.array(seg_adapter), np.array(rank), np.array(scale), plora.PLORA_BF16)
+def check(T, D, K, seg_off, seg_adapter, rank, scale, w_layout=0):
+    d = plora.Desc(T, D, K, np.array(seg_off), np.array(seg_adapter), np.array(rank), np.array(scale), plora.PLORA_BF16,
+                   w_layout)
     info, tabs, image = plora.plora_debug_metadata(d)
-    seg, ad, by_tokens, seg_list, blk_seg, tiles, h_elems, max_r16 = brute_force(T, D, seg_off, seg_adapter, rank)
+    seg, ad, by_tokens, seg_list, blk_seg, tiles, h_elems, max_r16 = brute_force(T, D, seg_off, seg_adapter, rank,
+                                                                                 K if w_layout else D)
     n_seg = len(seg_adapter)
     hdr = tabs["hdr"]
     assert (hdr["T"], hdr["D"], hdr["K"], hdr["n_seg"], hdr["n_adapters"]) == (T, D, K, n_seg, len(rank))
+    assert int(hdr["w_out_in"]) == w_layout and int(hdr["at_base"]) == 0
     assert hdr["n_blocks"] == len(blk_seg) == info.n_blocks and hdr["max_r16"] == max_r16 == info.max_r16
     assert info.h_elems == h_elems == plora.plora_h_elems(d)
     for s in range(n_seg):
@@ -77,6 +81,8 @@ def check(T, D, K, seg_off, seg_adapter, rank, scale):
             assert int(tabs["ad"][k][f]) == v, (k, f)
         assert float(tabs["ad"][k]["scale"]) == np.float32(scale[k])
         assert int(tabs["ad"][k]["by_tokens"]) == by_tokens[k]
+        # exported without pointers: B is null, the packed A^T buffer starts at address 0
+        assert int(tabs["ad"][k]["ext_b"]) == (2 * ad[k]["at_off"] if w_layout else 0)
     assert tabs["seg_list"].tolist() == seg_list
     assert tabs["blk_seg"].tolist() == blk_seg
     assert info.n_tiles == len(tiles)
@@ -89,6 +95,7 @@ def check(T, D, K, seg_off, seg_adapter, rank, scale):
             q = rec["s"][j]
             assert (int(q["row0"]), int(q["row1"]), int(q["rp"]), int(q["r"]), int(q["hb_off"]), int(q["ap_off"])) == \
                 (seg[s]["row0"], seg[s]["row1"], seg[s]["rp"], seg[s]["r"], seg[s]["hb_off"], ad[seg_adapter[s]]["ap_off"])
+            assert int(q["B"]) == (2 * ad[seg_adapter[s]]["at_off"] if w_layout else 0)
     # launch plans and workspace: ranges and sizes
     for v in (info.shrink_splits, info.dh_splits, info.da_splits, info.db_splits):
         assert 1 <= v <= 8
@@ -101,7 +108,7 @@ def check(T, D, K, seg_off, seg_adapter, rank, scale):
     assert info.ws_total == plora.plora_workspace_bytes(d)
     assert info.ws_desc - info.ws_meta >= info.table_bytes
     assert info.ws_ap - info.ws_at >= 2 * D * info.r16_total
-    assert info.ws_hb - info.ws_ap >= 2 * D * sum(pad(r, 64) for r in rank)
+    assert info.ws_hb - info.ws_ap >= 2 * (K if w_layout else D) * sum(pad(r, 64) for r in rank)
     hb_elems = sum((g["row1"] - g["row0"]) * g["rp"] for g in seg if g["adapter"] >= 0)
     zt_elems = sum(g["r16"] * g["lp"] for g in seg if g["adapter"] >= 0)
     assert info.ws_zt_h - info.ws_hb >= 2 * hb_elems
@@ -127,7 +134,8 @@ def test_tables_equal_brute_force_random_layouts(seed):
     seg_adapter = rng.integers(-1, n_ad, size=n_seg).tolist()       # base-only rows, repeated and unused adapters
     rank = rng.integers(1, 129, size=n_ad).tolist()
     scale = (rng.integers(1, 9, size=n_ad) / 4.0).tolist()
-    check(seg_off[-1], 8 * int(rng.integers(1, 40)), 8 * int(rng.integers(1, 40)), seg_off, seg_adapter, rank, scale)
+    check(seg_off[-1], 8 * int(rng.integers(1, 40)), 8 * int(rng.integers(1, 40)), seg_off, seg_adapter, rank, scale,
+          w_layout=seed % 2)
 
 
 def test_tables_many_blocks_and_tiny_segments():
