@@ -204,7 +204,7 @@ def main():
         torch.cuda.synchronize()
         kern = {}
         for name in plora.KERNEL_CLASSES:
-            if name == "adamw":
+            if name in ("adamw", "expand"):
                 continue
             ms, n = plora.plora_kernel_time(name)
             kern[name] = (ms / n) if n else None
@@ -316,6 +316,45 @@ def main():
                             "note": "plora_adamw_step over all A_k, B_k (two launches); reads and writes, so the read-only "
                                     "streaming ceiling does not apply"}
         del sA, sB
+        torch.cuda.empty_cache()
+
+    # the stand-alone low-rank calls (for callers with a base GEMM of their own): y and dx are updated in place
+    lora_only = None
+    if lin.dtype == "bf16" and lay.n_adapters > 0:
+        ws_lo = torch.empty(plora.plora_lora_workspace_bytes(run.desc), dtype=torch.uint8, device="cuda")
+        n_lo = 10
+        res = {}
+        sum_Lr = lay.sum_Lr()
+        R = int(sum(int(r) for r in lay.rank))
+        rows = int(sum(int(lay.seg_off[s_ + 1] - lay.seg_off[s_]) for s_ in range(lay.n_seg) if int(lay.seg_adapter[s_]) >= 0))
+
+        def lo_fwd(i):
+            plora.plora_lora_fwd(run.desc, run.xs[i % run.n_sets], run.A, run.B, run.y, run.h, ws_lo)
+
+        def lo_bwd(i):
+            plora.plora_lora_bwd(run.desc, run.xs[i % run.n_sets], run.A, run.B, run.dys[i % run.n_sets], run.h, run.dx,
+                                 run.dA, run.dB, ws_lo)
+
+        for name, fn, N_ in (("fwd", lo_fwd, K), ("bwd", lo_bwd, D)):
+            run.y.zero_()
+            run.dx.zero_()
+            ms_call = timed(fn, n_lo, 2)
+            plora.plora_set_kernel_timing(True)
+            for i in range(n_lo):
+                fn(i)
+            torch.cuda.synchronize()
+            ms_tot, n_br = plora.plora_kernel_time("expand")
+            plora.plora_set_kernel_timing(False)
+            ms_k = ms_tot / max(n_br, 1)
+            by = 2.0 * rows * N_ * 2 + sum_Lr * 2.0 + R * N_ * 2.0    # C read and written, low-rank factor, small matrices
+            a = by / (ms_k * 1e-3) / 1e9
+            res[name] = {"call_ms": round(ms_call, 4),
+                         "expand_kernel": {"ms": round(ms_k, 4), "bound": "hbm", "achieved": round(a, 1), "unit": "GB/s",
+                                           "frac": round(a / PEAK_HBM_GBS, 4), "algorithmic_bytes": int(by)}}
+        res["note"] = ("plora_lora_fwd: shrink + in-place update of y; plora_lora_bwd: dH, dB, dA + in-place update of dx; "
+                       "the update kernel reads and writes its output once")
+        lora_only = res
+        del ws_lo
         torch.cuda.empty_cache()
 
     # context: the vendor GEMM library on the same operands (not part of the metric)
@@ -528,6 +567,7 @@ def main():
         "kernels": kernels,
         "measured_ceilings": ceil,
         "rotation": rotation,
+        "lora_only": lora_only,
         "vendor_gemm": vendor,
         "sequential_adapters": sequential,
         "per_config": per_config,

@@ -173,6 +173,23 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
                               void *hip_stream);
 
 /*
+ * Stand-alone low-rank update, for callers that compute the base product themselves (another GEMM library, a
+ * quantised weight): the packed LoRA kernels beside the framework's base GEMM, as the paper runs them (section 2.4,
+ * appendix C.2).  Same packing, arguments and error codes as the fused calls, without W (desc->w_layout is not used):
+ *   plora_lora_fwd   y_t  += scale_k (x_t A_k) B_k     y  DEVICE [T][d_out], holds x W on entry, updated in place
+ *   plora_lora_bwd   dx_t += g_t A_k^T                 dx DEVICE [T][d_in], holds dy W^T on entry; NULL skips it
+ *                    dA_k, dB_k as plora_linear_bwd (overwritten)
+ * Rows of segments without an adapter are left as they are.  The sum is formed in fp32 (fp64 for PLORA_F32) and
+ * rounded once.  The workspace must hold plora_lora_workspace_bytes(desc) bytes (0 for an invalid description).
+ */
+size_t plora_lora_workspace_bytes(const plora_desc *desc);
+plora_status plora_lora_fwd(const plora_desc *desc, const void *x, const void *const *A, const void *const *B,
+                            void *y, float *h_saved, void *workspace, size_t ws_bytes, void *hip_stream);
+plora_status plora_lora_bwd(const plora_desc *desc, const void *x, const void *const *A, const void *const *B,
+                            const void *dy, const float *h_saved, void *dx, float *const *dA, float *const *dB,
+                            void *workspace, size_t ws_bytes, void *hip_stream);
+
+/*
  * Per-adapter optimizer step after a backward call (section 2.4: every adapter keeps its own
  * parameters and optimizer state; appendix B: AdamW with gradient, momentum and velocity per
  * adapter; Table 1: the learning rate is a per-job hyperparameter).  AdamW as published, in the

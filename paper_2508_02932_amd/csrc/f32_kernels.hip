@@ -129,6 +129,41 @@ __global__ void __launch_bounds__(256) k_f32_gemm(MetaView mv, const float *S, c
     }
 }
 
+// Stand-alone low-rank update: C[t][n] += mult * sum_j side[t][j] * op_k(j, n)   (fp64 accumulation)
+//   to_y : side = h (unscaled), op_k = B_k [r][N], mult = scale_k;   else side = g (carries scale_k), op_k = A_k^T, A_k [N][r]
+template <bool TO_Y>
+__global__ void __launch_bounds__(256) k_f32_expand(MetaView mv, float *C, int64_t N, const float *side)
+{
+    const int64_t t = (int64_t)blockIdx.x * 2 + threadIdx.x / 128;
+    const int64_t n = (int64_t)blockIdx.y * 128 + threadIdx.x % 128;
+    if (t >= mv.hdr->T || n >= N) return;
+    const int s = seg_of_row(mv, (int)t);
+    const SegInfo g = mv.seg[s];
+    if (g.adapter < 0) return;
+    const AdapterInfo a = mv.ad[g.adapter];
+    const float *row = side + g.h_off + (int64_t)(t - g.row0) * g.r;
+    double l = 0.0;
+    if (TO_Y) {
+        const float *Bk = static_cast<const float *>(a.B);
+        for (int q = 0; q < g.r; ++q) l += (double)row[q] * (double)Bk[(int64_t)q * N + n];
+        l *= (double)a.scale;
+    } else {
+        const float *Ak = static_cast<const float *>(a.A);
+        for (int q = 0; q < g.r; ++q) l += (double)row[q] * (double)Ak[n * g.r + q];
+    }
+    C[t * N + n] = (float)((double)C[t * N + n] + l);
+}
+
+hipError_t launch_f32_expand(const MetaView &mv, const MetaHeader &h, bool to_y, float *C, const float *side, hipStream_t st)
+{
+    if (h.T == 0 || h.n_blocks == 0) return hipSuccess;
+    const int64_t N = to_y ? h.K : h.D;
+    dim3 grid((unsigned)((h.T + 1) / 2), (unsigned)((N + 127) / 128));     // N <= 2^22: at most 32768 in y
+    if (to_y) hipLaunchKernelGGL(k_f32_expand<true>, grid, dim3(256), 0, st, mv, C, N, side);
+    else hipLaunchKernelGGL(k_f32_expand<false>, grid, dim3(256), 0, st, mv, C, N, side);
+    return hipGetLastError();
+}
+
 hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward, const float *S, const float *W,
                            const float *side, float *C, hipStream_t st)
 {

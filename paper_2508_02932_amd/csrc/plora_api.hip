@@ -81,7 +81,8 @@ struct HostMeta {
     std::vector<char> image;          // the tables as the device lays them out (pointer fields null)
     Tables t;
     MetaHeader hdr;
-    WorkspaceLayout ws;
+    WorkspaceLayout ws;               // plora_linear_fwd / _bwd
+    WorkspaceLayout ws_lora;          // plora_lora_fwd / _bwd: the padded small-matrix region holds [max(d_in, d_out)][rp]
     size_t h_elems = 0, hb_elems = 0, zt_elems = 0, at_elems = 0, ap_elems = 0;
     int r16_total = 0, n_active = 0, split_dA = 1, split_dB = 1, bc_dA = 256, bc_dB = 256;
     int split_shrink = 1, split_dh = 1;
@@ -128,27 +129,30 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     m.split_shrink = skinny_splits(m.hdr, d->d_in);
     m.split_dh = skinny_splits(m.hdr, d->d_out);
 
-    WorkspaceLayout &w = m.ws;
-    size_t o = 0;
-    w.zero = o; o += kZeroBytes;
-    w.meta_bytes = m.layout.bytes;
-    w.meta = o; o = align_up(o + w.meta_bytes, 256);
-    w.desc = o; o = align_up(o + (m.n_words > kChunkWords ? (size_t)m.n_words * 4 : 0), 256);
     const bool bf = d->dtype == PLORA_BF16;
-    w.at = o;   o = align_up(o + (bf ? m.at_elems * 2 : 0), 256);
-    w.ap = o;   o = align_up(o + (bf ? m.ap_elems * 2 : 0), 256);
-    w.hb = o;   o = align_up(o + (bf ? m.hb_elems * 2 : 0), 256);
-    w.zt_h = o; o = align_up(o + (bf ? m.zt_elems * 2 : 0), 256);
-    w.zt_g = o; o = align_up(o + (bf ? m.zt_elems * 2 : 0), 256);
-    w.hf = o;   o = align_up(o + m.h_elems * 4, 256);
-    w.gf = o;   o = align_up(o + (bf ? 0 : m.h_elems * 4), 256);
-    w.part = o; o = align_up(o + (bf ? (size_t)kSkinnyMaxSplits * m.hdr.n_blocks * kSkinnyRows * m.hdr.max_r16 * 4 : 0), 256);
-    {
+    auto lay_out = [&](WorkspaceLayout &w, size_t ap_elems) {
+        size_t o = 0;
+        w.zero = o; o += kZeroBytes;
+        w.meta_bytes = m.layout.bytes;
+        w.meta = o; o = align_up(o + w.meta_bytes, 256);
+        w.desc = o; o = align_up(o + (m.n_words > kChunkWords ? (size_t)m.n_words * 4 : 0), 256);
+        w.at = o;   o = align_up(o + (bf ? m.at_elems * 2 : 0), 256);
+        w.ap = o;   o = align_up(o + (bf ? ap_elems * 2 : 0), 256);
+        w.hb = o;   o = align_up(o + (bf ? m.hb_elems * 2 : 0), 256);
+        w.zt_h = o; o = align_up(o + (bf ? m.zt_elems * 2 : 0), 256);
+        w.zt_g = o; o = align_up(o + (bf ? m.zt_elems * 2 : 0), 256);
+        w.hf = o;   o = align_up(o + m.h_elems * 4, 256);
+        w.gf = o;   o = align_up(o + (bf ? 0 : m.h_elems * 4), 256);
+        w.part = o; o = align_up(o + (bf ? (size_t)kSkinnyMaxSplits * m.hdr.n_blocks * kSkinnyRows * m.hdr.max_r16 * 4 : 0), 256);
         const size_t a_bytes = m.split_dA > 1 ? (size_t)m.split_dA * m.r16_total * d->d_in * 4 : 0;
         const size_t b_bytes = m.split_dB > 1 ? (size_t)m.split_dB * m.r16_total * d->d_out * 4 : 0;
         w.wpart = o; o = align_up(o + (bf ? (a_bytes > b_bytes ? a_bytes : b_bytes) : 0), 256);
-    }
-    w.total = o + 256;
+        w.total = o + 256;
+    };
+    lay_out(m.ws, m.ap_elems);
+    int64_t rp_total = 0;
+    for (int32_t k = 0; k < d->n_adapters; ++k) rp_total += m.t.ad[k].rp;
+    lay_out(m.ws_lora, (size_t)(rp_total * std::max(d->d_in, d->d_out)));
 }
 
 // ---- metadata cache: the last few descriptions and what was derived from them ---------------------
@@ -195,7 +199,7 @@ static std::shared_ptr<const HostMeta> meta_of(const plora_desc *d)
 // ---- bench-only kernel timing (declared in plora_bench.h) -------------------------------------------
 // Every kernel class of a call is bracketed by a pair of HIP events recorded on the call's own
 // stream; pairs come from a pool that is filled while timing is enabled and summed on request.
-constexpr int kClasses = 8;
+constexpr int kClasses = 9;
 constexpr int kMaxPairs = 16384;
 static int g_timing = 0;
 static std::vector<hipEvent_t> g_pool;            // 2 events per pair, created on demand
@@ -225,20 +229,21 @@ static bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) &
 // One call's host state: the cached metadata and the compact description with this call's pointers.
 struct Call {
     std::shared_ptr<const HostMeta> m;
+    const WorkspaceLayout *L = nullptr;      // the workspace layout of this kind of call (inside *m)
     uint32_t small[kChunkWords];
     std::vector<uint32_t> large;
     const uint32_t *words = nullptr;
 };
 
-// Checks shared by forward and backward.
+// Checks shared by forward and backward.  lora_only: the stand-alone low-rank calls (no W, their own workspace layout).
 static plora_status prepare(const plora_desc *d, const void *x, const void *W, const void *const *A,
                             const void *const *B, float *const *dA, float *const *dB, void *workspace, size_t ws_bytes,
-                            Call &c)
+                            bool lora_only, Call &c)
 {
     plora_status st = validate(d);
     if (st != PLORA_OK) return st;
     if (!x && d->T > 0) return PLORA_ERR_NULL;
-    if (!W) return PLORA_ERR_NULL;
+    if (!W && !lora_only) return PLORA_ERR_NULL;
     if (d->n_adapters > 0 && (!A || !B)) return PLORA_ERR_NULL;
     for (int32_t k = 0; k < d->n_adapters; ++k) {
         if (!A[k] || !B[k]) return PLORA_ERR_NULL;
@@ -246,65 +251,78 @@ static plora_status prepare(const plora_desc *d, const void *x, const void *W, c
     }
     if (misaligned(x) || misaligned(W)) return PLORA_ERR_ALIGN;
     c.m = meta_of(d);
-    if (!workspace || ws_bytes < c.m->ws.total) return PLORA_ERR_WORKSPACE;
+    c.L = lora_only ? &c.m->ws_lora : &c.m->ws;
+    if (!workspace || ws_bytes < c.L->total) return PLORA_ERR_WORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
     uint32_t *w = c.small;
     if (c.m->n_words > kChunkWords) { c.large.resize((size_t)c.m->n_words); w = c.large.data(); }
-    fill_desc_words(d, c.m->hdr.n_blocks, A, B, dA, dB, static_cast<const char *>(workspace) + c.m->ws.at, w);
+    fill_desc_words(d, c.m->hdr.n_blocks, A, B, dA, dB, static_cast<const char *>(workspace) + c.L->at, w);
     c.words = w;
     return PLORA_OK;
 }
 
-static MetaView device_view(const HostMeta &m, char *ws)
+static MetaView device_view(const HostMeta &m, const WorkspaceLayout &L, char *ws)
 {
-    return view_of(tables_at(ws + m.ws.meta, m.layout));
+    return view_of(tables_at(ws + L.meta, m.layout));
 }
 
 static plora_status forward_impl(const plora_desc *desc, const void *x, const void *W, const void *const *A,
                                  const void *const *B, void *y, float *h_saved, void *workspace, size_t ws_bytes,
-                                 void *hip_stream)
+                                 void *hip_stream, bool lora_only = false)
 {
     Call c;
-    plora_status ps = prepare(desc, x, W, A, B, nullptr, nullptr, workspace, ws_bytes, c);
+    plora_status ps = prepare(desc, x, W, A, B, nullptr, nullptr, workspace, ws_bytes, lora_only, c);
     if (ps != PLORA_OK) return ps;
     const HostMeta &m = *c.m;
+    const WorkspaceLayout &L = *c.L;
     if (!y && desc->T > 0) return PLORA_ERR_NULL;
     if (misaligned(y) || misaligned(h_saved)) return PLORA_ERR_ALIGN;
     if (desc->T == 0) return PLORA_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
 
-    const MetaView mv = device_view(m, ws);
+    const MetaView mv = device_view(m, L, ws);
     const bool lora = m.hdr.n_blocks > 0;
     const bool bf = desc->dtype == PLORA_BF16;
     const bool w_out_in = m.hdr.w_out_in != 0;
     { Bracket b(6, st);
-      PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + m.ws.meta, reinterpret_cast<uint32_t *>(ws + m.ws.desc), ws + m.ws.zero,
-                         ws + m.ws.at, ws + m.ws.ap, bf && lora, false, bf && lora && w_out_in, nullptr, nullptr, st)); }
-    float *hf = h_saved ? h_saved : reinterpret_cast<float *>(ws + m.ws.hf);
+      PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + L.meta, reinterpret_cast<uint32_t *>(ws + L.desc), ws + L.zero,
+                         ws + L.at, ws + L.ap, bf && lora, false, bf && lora && (w_out_in || lora_only), nullptr, nullptr, st)); }
+    float *hf = h_saved ? h_saved : reinterpret_cast<float *>(ws + L.hf);
 
     if (desc->dtype == PLORA_F32) {
         const float *xf = static_cast<const float *>(x);
         if (lora) { Bracket b(2, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hf, st)); }
+        if (lora_only) {
+            Bracket b(8, st);
+            PL_TRY(launch_f32_expand(mv, m.hdr, true, static_cast<float *>(y), hf, st));
+            return PLORA_OK;
+        }
         { Bracket b(0, st);
           PL_TRY(launch_f32_gemm(mv, m.hdr, true, xf, static_cast<const float *>(W), hf, static_cast<float *>(y), st)); }
         return PLORA_OK;
     }
 
-    void *at = ws + m.ws.at, *hb = ws + m.ws.hb;
-    float *part = reinterpret_cast<float *>(ws + m.ws.part);
+    void *at = ws + L.at, *hb = ws + L.hb;
+    float *part = reinterpret_cast<float *>(ws + L.part);
     if (lora) {
         Bracket b(2, st);
-        PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, h_saved, hb, nullptr, false, st));
+        PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + L.zero, part, h_saved, hb, nullptr, false, st));
+    }
+    if (lora_only) {
+        // the padded buffer holds B_k^T [d_out][rp]; the tables carry its offsets for d_in rows unless W's layout says d_out
+        Bracket b(8, st);
+        PL_TRY(launch_expand_bf16(mv, m.hdr, y, desc->d_out, hb, ws + L.ap, w_out_in ? desc->d_out : desc->d_in, ws + L.zero, st));
+        return PLORA_OK;
     }
     { Bracket b(0, st);
-      PL_TRY(launch_gemm_bf16(mv, m.hdr, !w_out_in, desc->d_in, desc->d_out, x, W, hb, ws + m.ws.ap, ws + m.ws.zero, y, st)); }
+      PL_TRY(launch_gemm_bf16(mv, m.hdr, !w_out_in, desc->d_in, desc->d_out, x, W, hb, ws + L.ap, ws + L.zero, y, st)); }
     return PLORA_OK;
 }
 
 static plora_status backward_impl(const plora_desc *desc, const void *x, const void *W, const void *const *A,
                                   const void *const *B, const void *dy, const float *h_saved, void *dx, float *const *dA,
-                                  float *const *dB, void *workspace, size_t ws_bytes, void *hip_stream)
+                                  float *const *dB, void *workspace, size_t ws_bytes, void *hip_stream, bool lora_only = false)
 {
     const bool want_w = (dA != nullptr) || (dB != nullptr);
     if (desc && want_w && desc->n_adapters > 0 && (!dA || !dB)) {
@@ -312,9 +330,10 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
         return v != PLORA_OK ? v : PLORA_ERR_NULL;
     }
     Call c;
-    plora_status ps = prepare(desc, x, W, A, B, want_w ? dA : nullptr, want_w ? dB : nullptr, workspace, ws_bytes, c);
+    plora_status ps = prepare(desc, x, W, A, B, want_w ? dA : nullptr, want_w ? dB : nullptr, workspace, ws_bytes, lora_only, c);
     if (ps != PLORA_OK) return ps;
     const HostMeta &m = *c.m;
+    const WorkspaceLayout &L = *c.L;
     if (!dy && desc->T > 0) return PLORA_ERR_NULL;
     if (misaligned(dy) || misaligned(dx) || misaligned(h_saved)) return PLORA_ERR_ALIGN;
     if (want_w && desc->n_adapters > 0) {
@@ -329,26 +348,27 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
     const bool any_w = want_w && desc->n_adapters > 0;
     if (desc->T == 0 && !any_w) return PLORA_OK;
 
-    const MetaView mv = device_view(m, ws);
+    const MetaView mv = device_view(m, L, ws);
     {
         const bool bf = desc->dtype == PLORA_BF16;
         const bool need_shrink = any_w && !h_saved;
         const bool tr = bf && lora && any_w && h_saved;
         // the low-rank operand of the dX GEMM: padded A_k, or - W stored [d_out][d_in] - the packed A_k^T
-        const bool dx_ap = dx != nullptr && !m.hdr.w_out_in, dx_at = dx != nullptr && m.hdr.w_out_in;
+        // (the stand-alone low-rank update always reads the padded A_k)
+        const bool dx_ap = dx != nullptr && (lora_only || !m.hdr.w_out_in), dx_at = dx != nullptr && !lora_only && m.hdr.w_out_in;
         Bracket b(6, st);
-        PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + m.ws.meta, reinterpret_cast<uint32_t *>(ws + m.ws.desc), ws + m.ws.zero,
-                           ws + m.ws.at, ws + m.ws.ap, bf && lora && (need_shrink || dx_at), bf && lora && dx_ap, false,
-                           tr ? h_saved : nullptr, tr ? ws + m.ws.zt_h : nullptr, st));
+        PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + L.meta, reinterpret_cast<uint32_t *>(ws + L.desc), ws + L.zero,
+                           ws + L.at, ws + L.ap, bf && lora && (need_shrink || dx_at), bf && lora && dx_ap, false,
+                           tr ? h_saved : nullptr, tr ? ws + L.zt_h : nullptr, st));
     }
 
     if (desc->dtype == PLORA_F32) {
         const float *xf = static_cast<const float *>(x), *dyf = static_cast<const float *>(dy);
-        float *gf = reinterpret_cast<float *>(ws + m.ws.gf);
+        float *gf = reinterpret_cast<float *>(ws + L.gf);
         const float *hf = h_saved;
         if (lora && any_w && !hf) {
             Bracket b(2, st);
-            float *hw = reinterpret_cast<float *>(ws + m.ws.hf);
+            float *hw = reinterpret_cast<float *>(ws + L.hf);
             PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hw, st));
             hf = hw;
         }
@@ -357,32 +377,39 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
             { Bracket b(4, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, false, dyf, desc->d_out, hf, st)); }
             { Bracket b(5, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, true, xf, desc->d_in, gf, st)); }
         }
-        if (dx && desc->T > 0) {
+        if (dx && desc->T > 0 && lora_only) {
+            Bracket b(8, st);
+            PL_TRY(launch_f32_expand(mv, m.hdr, false, static_cast<float *>(dx), gf, st));
+        } else if (dx && desc->T > 0) {
             Bracket b(1, st);
             PL_TRY(launch_f32_gemm(mv, m.hdr, false, dyf, static_cast<const float *>(W), gf, static_cast<float *>(dx), st));
         }
         return PLORA_OK;
     }
 
-    void *at = ws + m.ws.at, *ap = ws + m.ws.ap, *gb = ws + m.ws.hb;
-    void *zt_h = ws + m.ws.zt_h, *zt_g = ws + m.ws.zt_g;
-    float *part = reinterpret_cast<float *>(ws + m.ws.part);
-    float *wpart = reinterpret_cast<float *>(ws + m.ws.wpart);
+    void *at = ws + L.at, *ap = ws + L.ap, *gb = ws + L.hb;
+    void *zt_h = ws + L.zt_h, *zt_g = ws + L.zt_g;
+    float *part = reinterpret_cast<float *>(ws + L.part);
+    float *wpart = reinterpret_cast<float *>(ws + L.wpart);
     if (lora) {
         if (any_w && !h_saved) {
             Bracket b(2, st);
-            PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + m.ws.zero, part, nullptr, nullptr, zt_h, false, st));
+            PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + L.zero, part, nullptr, nullptr, zt_h, false, st));
         }
         { Bracket b(3, st);
-          PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, ws + m.ws.zero, part, nullptr, gb, any_w ? zt_g : nullptr, true, st)); }
+          PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, ws + L.zero, part, nullptr, gb, any_w ? zt_g : nullptr, true, st)); }
     }
     if (any_w) {
-        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + m.ws.zero, wpart, m.split_dB, m.r16_total, m.n_active, st)); }
-        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + m.ws.zero, wpart, m.split_dA, m.r16_total, m.n_active, st)); }
+        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + L.zero, wpart, m.split_dB, m.r16_total, m.n_active, st)); }
+        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + L.zero, wpart, m.split_dA, m.r16_total, m.n_active, st)); }
     }
-    if (dx && desc->T > 0) {
+    if (dx && desc->T > 0 && lora_only) {
+        // padded A_k [d_in][rp]; the tables carry its offsets for d_in rows unless W's layout says d_out
+        Bracket b(8, st);
+        PL_TRY(launch_expand_bf16(mv, m.hdr, dx, desc->d_in, gb, ap, m.hdr.w_out_in ? desc->d_out : desc->d_in, ws + L.zero, st));
+    } else if (dx && desc->T > 0) {
         Bracket b(1, st);
-        PL_TRY(launch_gemm_bf16(mv, m.hdr, m.hdr.w_out_in != 0, desc->d_out, desc->d_in, dy, W, gb, ap, ws + m.ws.zero, dx, st));
+        PL_TRY(launch_gemm_bf16(mv, m.hdr, m.hdr.w_out_in != 0, desc->d_out, desc->d_in, dy, W, gb, ap, ws + L.zero, dx, st));
     }
     return PLORA_OK;
 }
@@ -611,6 +638,31 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
 {
     PL_GUARDED(PLORA_ERR_INTERNAL,
         return backward_impl(desc, x, W, A, B, dy, h_saved, dx, dA, dB, workspace, ws_bytes, hip_stream);
+    )
+}
+
+size_t plora_lora_workspace_bytes(const plora_desc *desc)
+{
+    PL_GUARDED(0,
+        if (validate(desc) != PLORA_OK) return 0;
+        return meta_of(desc)->ws_lora.total;
+    )
+}
+
+plora_status plora_lora_fwd(const plora_desc *desc, const void *x, const void *const *A, const void *const *B, void *y,
+                            float *h_saved, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        return forward_impl(desc, x, nullptr, A, B, y, h_saved, workspace, ws_bytes, hip_stream, true);
+    )
+}
+
+plora_status plora_lora_bwd(const plora_desc *desc, const void *x, const void *const *A, const void *const *B,
+                            const void *dy, const float *h_saved, void *dx, float *const *dA, float *const *dB,
+                            void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        return backward_impl(desc, x, nullptr, A, B, dy, h_saved, dx, dA, dB, workspace, ws_bytes, hip_stream, true);
     )
 }
 

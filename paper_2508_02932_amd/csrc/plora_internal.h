@@ -382,6 +382,10 @@ hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode,
 hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool w_rows_contract, int64_t Kd, int64_t N,
                             const void *S, const void *W, const void *side, const void *ap, const void *zero, void *C,
                             hipStream_t st);
+// Stand-alone low-rank update C[T][N] += side * op_k (bf16, one rounding): side = bf16 low-rank factor [len][rp] per
+// segment, opT = padded small matrices [N][rp] (adapter k at N * (ap_off_k / table_rows)).
+hipError_t launch_expand_bf16(const MetaView &mv, const MetaHeader &h, void *C, int64_t N, const void *side, const void *opT,
+                              int64_t table_rows, const void *zero, hipStream_t st);
 // Token contraction: out_k = mult * sum_t S[t][c] * zt[j][t] over all segments of adapter k.
 //   want_dA: S = x, out = dA_k[c][j], mult = 1;  else S = dy, out = dB_k[j][c], mult = scale_k.
 //   n_split > 1: the token walk is split, partial tiles go through `part` ([split][r16_total][C] fp32).
@@ -397,6 +401,8 @@ hipError_t launch_f32_lowrank(const MetaView &mv, const MetaHeader &h, int mode,
                               float *out, hipStream_t st);
 hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward, const float *S, const float *W,
                            const float *side, float *C, hipStream_t st);   // W's layout: h.w_out_in
+// to_y: y += scale_k h B_k (side = h);  else dx += g A_k^T (side = g, which carries scale_k).
+hipError_t launch_f32_expand(const MetaView &mv, const MetaHeader &h, bool to_y, float *C, const float *side, hipStream_t st);
 hipError_t launch_f32_wgrad(const MetaView &mv, const MetaHeader &h, bool want_dA, const float *S, int64_t C,
                             const float *side, hipStream_t st);
 

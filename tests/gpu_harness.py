@@ -76,11 +76,12 @@ class DeviceProblem:
     guards: list
 
 
-def upload(lin: wl.Linear, t: wl.Tensors, w_layout: int = 0) -> DeviceProblem:
-    """w_layout = plora.PLORA_W_OUT_IN hands the library W stored [d_out][d_in] (the same matrix, transposed in memory)."""
+def upload(lin: wl.Linear, t: wl.Tensors, w_layout: int = 0, lora_only: bool = False) -> DeviceProblem:
+    """w_layout = plora.PLORA_W_OUT_IN hands the library W stored [d_out][d_in] (the same matrix, transposed in memory);
+    lora_only sizes the workspace for the stand-alone low-rank calls."""
     d = desc_of(lin, w_layout)
     tdt = torch.bfloat16 if lin.dtype == "bf16" else torch.float32
-    ws_bytes = plora.plora_workspace_bytes(d)
+    ws_bytes = plora.plora_lora_workspace_bytes(d) if lora_only else plora.plora_workspace_bytes(d)
     assert ws_bytes > 0
     nan = float("nan")
     T, D, K = lin.layout.T, lin.D, lin.K
@@ -123,3 +124,14 @@ def ragged_h_to_rows(lin: wl.Linear, h_flat: np.ndarray) -> np.ndarray:
         out[lo:hi, :r] = h_flat[off:off + (hi - lo) * r].reshape(hi - lo, r)
         off += (hi - lo) * r
     return out
+
+
+def lora_forward(p: DeviceProblem, save_h: bool = True):
+    """Stand-alone low-rank forward: p.y must hold the base product on entry."""
+    plora.plora_lora_fwd(p.desc, p.x, p.A, p.B, p.y, p.h if save_h else None, p.ws)
+
+
+def lora_backward(p: DeviceProblem, use_saved_h: bool = True, want_dx: bool = True, want_w: bool = True):
+    """Stand-alone low-rank backward: p.dx must hold dy W^T on entry."""
+    plora.plora_lora_bwd(p.desc, p.x, p.A, p.B, p.dy, p.h if use_saved_h else None, p.dx if want_dx else None,
+                         p.dA if want_w else None, p.dB if want_w else None, p.ws)
