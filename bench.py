@@ -204,7 +204,7 @@ def main():
         torch.cuda.synchronize()
         kern = {}
         for name in plora.KERNEL_CLASSES:
-            if name in ("adamw", "expand"):
+            if name in ("adamw", "expand", "nf4"):
                 continue
             ms, n = plora.plora_kernel_time(name)
             kern[name] = (ms / n) if n else None
@@ -355,6 +355,40 @@ def main():
                        "the update kernel reads and writes its output once")
         lora_only = res
         del ws_lo
+        torch.cuda.empty_cache()
+
+    # the same step on a base weight stored in 4 bits (NF4): every call first expands W into the workspace
+    nf4_base = None
+    if lin.dtype == "bf16" and (D * K) % 64 == 0 and w_layout != 2:
+        codes_h, absmax_h = wl.nf4_storage(D * K, D, seed=args.config)
+        codes_d, absmax_d = torch.from_numpy(codes_h).cuda(), torch.from_numpy(absmax_h).cuda()
+        del codes_h, absmax_h
+        ws_q = torch.empty(plora.plora_nf4_workspace_bytes(run.desc), dtype=torch.uint8, device="cuda")
+        n_q = max(4, args.steps // 2)
+
+        def q_step(i):
+            plora.plora_linear_fwd_nf4(run.desc, run.xs[i % run.n_sets], codes_d, absmax_d, run.A, run.B, run.y, run.h, ws_q)
+            plora.plora_linear_bwd_nf4(run.desc_bwd, run.xs[i % run.n_sets], codes_d, absmax_d, run.A, run.B,
+                                       run.dys[i % run.n_sets], run.h, run.dx, run.dA, run.dB, ws_q)
+
+        ms_q = timed(q_step, n_q, 2)
+        plora.plora_set_kernel_timing(True)
+        for i in range(n_q):
+            q_step(i)
+        torch.cuda.synchronize()
+        ms_tot, n_br = plora.plora_kernel_time("nf4")
+        plora.plora_set_kernel_timing(False)
+        ms_k = ms_tot / max(n_br, 1)
+        by = D * K * (0.5 + 4.0 / 64 + 2.0)      # indices and block constants read, bf16 values written
+        a = by / (ms_k * 1e-3) / 1e9
+        nf4_base = {"ms_per_step": round(ms_q, 4), "tflops": round(flops / (ms_q * 1e-3) / 1e12, 1),
+                    "slowdown_vs_bf16_weight": round(ms_q / ms_per_step, 4),
+                    "dequant_kernel": {"ms": round(ms_k, 4), "bound": "hbm", "achieved": round(a, 1), "unit": "GB/s",
+                                       "frac": round(a / PEAK_HBM_GBS, 4), "algorithmic_bytes": int(by)},
+                    "weight_bytes": {"nf4": int(D * K * (0.5 + 4.0 / 64)), "bf16": int(D * K * 2)},
+                    "note": "plora_linear_fwd_nf4 + plora_linear_bwd_nf4 (two expansions per step); synthetic indices and "
+                            "block constants; the stored weight is read as W" + ("[d_out][d_in]" if w_layout == 1 else "[d_in][d_out]")}
+        del codes_d, absmax_d, ws_q
         torch.cuda.empty_cache()
 
     # context: the vendor GEMM library on the same operands (not part of the metric)
@@ -568,6 +602,7 @@ def main():
         "measured_ceilings": ceil,
         "rotation": rotation,
         "lora_only": lora_only,
+        "nf4_base": nf4_base,
         "vendor_gemm": vendor,
         "sequential_adapters": sequential,
         "per_config": per_config,

@@ -190,6 +190,32 @@ plora_status plora_lora_bwd(const plora_desc *desc, const void *x, const void *c
                             void *workspace, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The layer on a base weight stored as 4-bit NormalFloat (NF4, the storage QLoRA publishes; the paper applies packed
+ * LoRA to such a base and notes that the LoRA computation does not change).  Storage of W, flat in the memory order
+ * that desc->w_layout names: blocks of 64 consecutive elements; per block one fp32 constant (its largest magnitude);
+ * per element a 4-bit index into the 16 levels of the format, two per byte, the element with the even position in the
+ * high half.  An element is level[index] * constant, formed in fp32 and, for PLORA_BF16, rounded to nearest even.
+ *   W_codes   DEVICE [d_in * d_out / 2] bytes, 16-byte aligned
+ *   W_absmax  DEVICE [d_in * d_out / 64] fp32, 16-byte aligned
+ * d_in * d_out must be a multiple of 64 (PLORA_ERR_SHAPE otherwise).
+ *
+ * plora_nf4_dequantize writes the n_elems values (a multiple of 64; dtype: plora_dtype of `out`) and is all a caller
+ * needs who wants to keep the expanded weight.  plora_linear_fwd_nf4 / _bwd_nf4 are plora_linear_fwd / _bwd on the
+ * stored weight: they expand W into the workspace first (the backward call only if dx is wanted), so the workspace
+ * must hold plora_nf4_workspace_bytes(desc) bytes; everything else is as for those calls.
+ */
+size_t plora_nf4_workspace_bytes(const plora_desc *desc);
+plora_status plora_nf4_dequantize(const void *W_codes, const float *W_absmax, int64_t n_elems, int32_t dtype,
+                                  void *out, void *hip_stream);
+plora_status plora_linear_fwd_nf4(const plora_desc *desc, const void *x, const void *W_codes, const float *W_absmax,
+                                  const void *const *A, const void *const *B, void *y, float *h_saved,
+                                  void *workspace, size_t ws_bytes, void *hip_stream);
+plora_status plora_linear_bwd_nf4(const plora_desc *desc, const void *x, const void *W_codes, const float *W_absmax,
+                                  const void *const *A, const void *const *B, const void *dy, const float *h_saved,
+                                  void *dx, float *const *dA, float *const *dB, void *workspace, size_t ws_bytes,
+                                  void *hip_stream);
+
+/*
  * Per-adapter optimizer step after a backward call (section 2.4: every adapter keeps its own
  * parameters and optimizer state; appendix B: AdamW with gradient, momentum and velocity per
  * adapter; Table 1: the learning rate is a per-job hyperparameter).  AdamW as published, in the

@@ -9,7 +9,7 @@
  * Classes: 0 base GEMM forward (with the fused expand), 1 dX GEMM (with the fused low-rank term),
  * 2 shrink, 3 dH, 4 dB, 5 dA, 6 the preparation launch (metadata, packing of A_k, conversion of a
  * saved activation), 7 the optimizer step (all launches of one plora_adamw_step call), 8 the stand-alone
- * low-rank update of plora_lora_fwd / plora_lora_bwd.
+ * low-rank update of plora_lora_fwd / plora_lora_bwd, 9 the expansion of an NF4 base weight.
  * Returns 0, or -1 on a bad argument or event error.  Process-global state, NOT thread-safe: one
  * benchmarking thread only, and no timed call may run concurrently with these two functions.
  */

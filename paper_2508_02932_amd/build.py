@@ -13,7 +13,7 @@ OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libplora.so")
 BENCH_LIB = os.path.join(HERE, "libplora_bench.so")      # ceiling microkernels for bench.py, not the product
 SOURCES = ["plora_api.hip", "small_kernels.hip", "f32_kernels.hip", "skinny_bf16.hip",
-           "gemm_bf16.hip", "tokcontract_bf16.hip", "adamw.hip", "expand_bf16.hip"]
+           "gemm_bf16.hip", "tokcontract_bf16.hip", "adamw.hip", "expand_bf16.hip", "nf4.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]

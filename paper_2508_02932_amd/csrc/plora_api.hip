@@ -199,7 +199,7 @@ static std::shared_ptr<const HostMeta> meta_of(const plora_desc *d)
 // ---- bench-only kernel timing (declared in plora_bench.h) -------------------------------------------
 // Every kernel class of a call is bracketed by a pair of HIP events recorded on the call's own
 // stream; pairs come from a pool that is filled while timing is enabled and summed on request.
-constexpr int kClasses = 9;
+constexpr int kClasses = 10;
 constexpr int kMaxPairs = 16384;
 static int g_timing = 0;
 static std::vector<hipEvent_t> g_pool;            // 2 events per pair, created on demand
@@ -268,7 +268,7 @@ static MetaView device_view(const HostMeta &m, const WorkspaceLayout &L, char *w
 
 static plora_status forward_impl(const plora_desc *desc, const void *x, const void *W, const void *const *A,
                                  const void *const *B, void *y, float *h_saved, void *workspace, size_t ws_bytes,
-                                 void *hip_stream, bool lora_only = false)
+                                 void *hip_stream, bool lora_only = false, bool check_only = false)
 {
     Call c;
     plora_status ps = prepare(desc, x, W, A, B, nullptr, nullptr, workspace, ws_bytes, lora_only, c);
@@ -277,7 +277,7 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
     const WorkspaceLayout &L = *c.L;
     if (!y && desc->T > 0) return PLORA_ERR_NULL;
     if (misaligned(y) || misaligned(h_saved)) return PLORA_ERR_ALIGN;
-    if (desc->T == 0) return PLORA_OK;
+    if (desc->T == 0 || check_only) return PLORA_OK;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     char *ws = static_cast<char *>(workspace);
 
@@ -322,7 +322,8 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
 
 static plora_status backward_impl(const plora_desc *desc, const void *x, const void *W, const void *const *A,
                                   const void *const *B, const void *dy, const float *h_saved, void *dx, float *const *dA,
-                                  float *const *dB, void *workspace, size_t ws_bytes, void *hip_stream, bool lora_only = false)
+                                  float *const *dB, void *workspace, size_t ws_bytes, void *hip_stream, bool lora_only = false,
+                                  bool check_only = false)
 {
     const bool want_w = (dA != nullptr) || (dB != nullptr);
     if (desc && want_w && desc->n_adapters > 0 && (!dA || !dB)) {
@@ -346,7 +347,7 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
     char *ws = static_cast<char *>(workspace);
     const bool lora = m.hdr.n_blocks > 0;
     const bool any_w = want_w && desc->n_adapters > 0;
-    if (desc->T == 0 && !any_w) return PLORA_OK;
+    if ((desc->T == 0 && !any_w) || check_only) return PLORA_OK;
 
     const MetaView mv = device_view(m, L, ws);
     {
@@ -638,6 +639,90 @@ plora_status plora_linear_bwd(const plora_desc *desc, const void *x, const void 
 {
     PL_GUARDED(PLORA_ERR_INTERNAL,
         return backward_impl(desc, x, W, A, B, dy, h_saved, dx, dA, dB, workspace, ws_bytes, hip_stream);
+    )
+}
+
+// Workspace of the NF4 calls: the ordinary workspace, then the expanded weight.
+static size_t nf4_weight_offset(const HostMeta &m) { return align_up(m.ws.total, 256); }
+static size_t nf4_weight_bytes(const plora_desc *d) { return (size_t)d->d_in * (size_t)d->d_out * (d->dtype == PLORA_BF16 ? 2 : 4); }
+
+size_t plora_nf4_workspace_bytes(const plora_desc *desc)
+{
+    PL_GUARDED(0,
+        if (validate(desc) != PLORA_OK || (desc->d_in * desc->d_out) % 64 != 0) return 0;
+        return nf4_weight_offset(*meta_of(desc)) + nf4_weight_bytes(desc);
+    )
+}
+
+plora_status plora_nf4_dequantize(const void *W_codes, const float *W_absmax, int64_t n_elems, int32_t dtype, void *out,
+                                  void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        if (dtype != PLORA_BF16 && dtype != PLORA_F32) return PLORA_ERR_UNSUPPORTED;
+        if (n_elems < 0 || n_elems % 64 != 0) return PLORA_ERR_SHAPE;
+        if (n_elems == 0) return PLORA_OK;
+        if (!W_codes || !W_absmax || !out) return PLORA_ERR_NULL;
+        if (misaligned(W_codes) || misaligned(W_absmax) || misaligned(out)) return PLORA_ERR_ALIGN;
+        hipStream_t st = static_cast<hipStream_t>(hip_stream);
+        Bracket b(9, st);
+        PL_TRY(launch_nf4_dequant(W_codes, W_absmax, n_elems, dtype == PLORA_BF16, out, st));
+        return PLORA_OK;
+    )
+}
+
+// Checks of the NF4 calls that come before anything is enqueued; *w_out = where the expanded weight goes.
+static plora_status nf4_prepare(const plora_desc *desc, const void *codes, const float *absmax, void *workspace,
+                                size_t ws_bytes, void **w_out, size_t *inner_bytes)
+{
+    const plora_status v = validate(desc);
+    if (v != PLORA_OK) return v;
+    if ((desc->d_in * desc->d_out) % 64 != 0) return PLORA_ERR_SHAPE;
+    if (!codes || !absmax) return PLORA_ERR_NULL;
+    if (misaligned(codes) || misaligned(absmax)) return PLORA_ERR_ALIGN;
+    const size_t off = nf4_weight_offset(*meta_of(desc));
+    if (!workspace || ws_bytes < off + nf4_weight_bytes(desc)) return PLORA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
+    *w_out = static_cast<char *>(workspace) + off;
+    *inner_bytes = off;
+    return PLORA_OK;
+}
+
+plora_status plora_linear_fwd_nf4(const plora_desc *desc, const void *x, const void *W_codes, const float *W_absmax,
+                                  const void *const *A, const void *const *B, void *y, float *h_saved, void *workspace,
+                                  size_t ws_bytes, void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        void *W = nullptr;
+        size_t inner = 0;
+        plora_status ps = nf4_prepare(desc, W_codes, W_absmax, workspace, ws_bytes, &W, &inner);
+        if (ps != PLORA_OK) return ps;
+        // every other argument is checked before the weight is expanded, so that an error enqueues nothing
+        ps = forward_impl(desc, x, W, A, B, y, h_saved, workspace, inner, hip_stream, false, true);
+        if (ps != PLORA_OK) return ps;
+        if (desc->T > 0) {
+            ps = plora_nf4_dequantize(W_codes, W_absmax, desc->d_in * desc->d_out, desc->dtype, W, hip_stream);
+            if (ps != PLORA_OK) return ps;
+        }
+        return forward_impl(desc, x, W, A, B, y, h_saved, workspace, inner, hip_stream);
+    )
+}
+
+plora_status plora_linear_bwd_nf4(const plora_desc *desc, const void *x, const void *W_codes, const float *W_absmax,
+                                  const void *const *A, const void *const *B, const void *dy, const float *h_saved, void *dx,
+                                  float *const *dA, float *const *dB, void *workspace, size_t ws_bytes, void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        void *W = nullptr;
+        size_t inner = 0;
+        plora_status ps = nf4_prepare(desc, W_codes, W_absmax, workspace, ws_bytes, &W, &inner);
+        if (ps != PLORA_OK) return ps;
+        ps = backward_impl(desc, x, W, A, B, dy, h_saved, dx, dA, dB, workspace, inner, hip_stream, false, true);
+        if (ps != PLORA_OK) return ps;
+        if (dx && desc->T > 0) {
+            ps = plora_nf4_dequantize(W_codes, W_absmax, desc->d_in * desc->d_out, desc->dtype, W, hip_stream);
+            if (ps != PLORA_OK) return ps;
+        }
+        return backward_impl(desc, x, W, A, B, dy, h_saved, dx, dA, dB, workspace, inner, hip_stream);
     )
 }
 

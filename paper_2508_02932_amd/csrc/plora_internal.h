@@ -406,6 +406,9 @@ hipError_t launch_f32_expand(const MetaView &mv, const MetaHeader &h, bool to_y,
 hipError_t launch_f32_wgrad(const MetaView &mv, const MetaHeader &h, bool want_dA, const float *S, int64_t C,
                             const float *side, hipStream_t st);
 
+// NF4 base weight: out[i] = level[index_i] * absmax[i / 64] for n_elems elements (a multiple of 64), bf16 or fp32.
+hipError_t launch_nf4_dequant(const void *codes, const float *absmax, int64_t n_elems, bool bf16, void *out, hipStream_t st);
+
 // optimizer ----------------------------------------------------------------------------------------
 struct AdamwTensor {
     void *param; float *master; const float *grad; float *m, *v;

@@ -21,12 +21,13 @@ PLORA_BF16, PLORA_F32 = 0, 1
 PLORA_W_IN_OUT, PLORA_W_OUT_IN = 0, 1
 PLORA_OK = 0
 PLORA_MAX_RANK, PLORA_MAX_ADAPTERS, PLORA_MAX_SEGMENTS = 128, 256, 1024
-KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "prep": 6, "adamw": 7, "expand": 8}
+KERNEL_CLASSES = {"gemm_fwd": 0, "gemm_dx": 1, "shrink": 2, "dh": 3, "db": 4, "da": 5, "prep": 6, "adamw": 7, "expand": 8, "nf4": 9}
 
 EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_workspace_bytes",
            "plora_build_metadata", "plora_linear_fwd", "plora_linear_fwd_noalloc", "plora_linear_bwd",
            "plora_set_kernel_timing", "plora_kernel_time", "plora_debug_metadata", "plora_adamw_step",
-           "plora_lora_workspace_bytes", "plora_lora_fwd", "plora_lora_bwd"]
+           "plora_lora_workspace_bytes", "plora_lora_fwd", "plora_lora_bwd",
+           "plora_nf4_workspace_bytes", "plora_nf4_dequantize", "plora_linear_fwd_nf4", "plora_linear_bwd_nf4"]
 
 
 class PloraError(RuntimeError):
@@ -108,6 +109,14 @@ def lib():
         L.plora_lora_fwd.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 6 + [C.c_size_t, C.c_void_p]
         L.plora_lora_bwd.restype = C.c_int
         L.plora_lora_bwd.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 9 + [C.c_size_t, C.c_void_p]
+        L.plora_nf4_workspace_bytes.restype = C.c_size_t
+        L.plora_nf4_workspace_bytes.argtypes = [C.POINTER(plora_desc)]
+        L.plora_nf4_dequantize.restype = C.c_int
+        L.plora_nf4_dequantize.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_void_p]
+        L.plora_linear_fwd_nf4.restype = C.c_int
+        L.plora_linear_fwd_nf4.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 8 + [C.c_size_t, C.c_void_p]
+        L.plora_linear_bwd_nf4.restype = C.c_int
+        L.plora_linear_bwd_nf4.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
         L.plora_set_kernel_timing.restype = None
         L.plora_set_kernel_timing.argtypes = [C.c_int]
         L.plora_kernel_time.restype = C.c_int
@@ -283,6 +292,35 @@ def plora_lora_bwd(d: Desc, x, A: Sequence, B: Sequence, dy, h_saved, dx, dA: Op
     kdb, pdb = _ptr_table(dB)
     _check(lib().plora_lora_bwd(d.ref, _ptr(x), pa, pb, _ptr(dy), _ptr(h_saved), _ptr(dx), pda, pdb, _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def plora_nf4_workspace_bytes(d: Desc) -> int:
+    return int(lib().plora_nf4_workspace_bytes(d.ref))
+
+
+def plora_nf4_dequantize(codes, absmax, n_elems: int, dtype: int, out, stream=None) -> None:
+    """Enqueues the expansion of an NF4 weight: out[i] = level[index_i] * absmax[i // 64]."""
+    _check(lib().plora_nf4_dequantize(_ptr(codes), _ptr(absmax), int(n_elems), int(dtype), _ptr(out), _stream(stream)))
+
+
+def plora_linear_fwd_nf4(d: Desc, x, W_codes, W_absmax, A: Sequence, B: Sequence, y, h_saved, workspace, stream=None) -> None:
+    """plora_linear_fwd on an NF4 base weight (expanded into the workspace first)."""
+    ka, pa = _ptr_table(A)
+    kb, pb = _ptr_table(B)
+    _check(lib().plora_linear_fwd_nf4(d.ref, _ptr(x), _ptr(W_codes), _ptr(W_absmax), pa, pb, _ptr(y), _ptr(h_saved),
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def plora_linear_bwd_nf4(d: Desc, x, W_codes, W_absmax, A: Sequence, B: Sequence, dy, h_saved, dx,
+                         dA: Optional[Sequence], dB: Optional[Sequence], workspace, stream=None) -> None:
+    """plora_linear_bwd on an NF4 base weight."""
+    ka, pa = _ptr_table(A)
+    kb, pb = _ptr_table(B)
+    kda, pda = _ptr_table(dA)
+    kdb, pdb = _ptr_table(dB)
+    _check(lib().plora_linear_bwd_nf4(d.ref, _ptr(x), _ptr(W_codes), _ptr(W_absmax), pa, pb, _ptr(dy), _ptr(h_saved),
+                                      _ptr(dx), pda, pdb, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)))
 
 
 def plora_adamw_step(d: Desc, A_side: dict, B_side: dict, hparams: Sequence, stream=None) -> None:

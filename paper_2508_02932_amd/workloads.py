@@ -212,3 +212,15 @@ def small(name: str, dtype: str, D: int, K: int, lengths: Sequence[int],
     lay = Layout(off, np.asarray(seg_adapter, dtype=np.int32), np.asarray(ranks, dtype=np.int32),
                  np.asarray(scales, dtype=np.float32))
     return Linear(name, dtype, D, K, lay, var_B, BASE_SEED + 77000 + seed)
+
+
+def nf4_storage(n_elems: int, d_in: int, seed: int):
+    """Synthetic 4-bit storage of a base weight with n_elems elements (a multiple of 64): uniformly random indices, two
+    per byte, and per-block constants around 1.8 / sqrt(d_in), which gives the stored values about the variance
+    1 / d_in of the dense synthetic weights (the 16 levels have a mean square of 0.30).  Returns (codes uint8
+    [n_elems / 2], absmax fp32 [n_elems / 64]); nothing here knows the levels."""
+    assert n_elems % 64 == 0
+    rng = np.random.default_rng(BASE_SEED + 7919 * seed + 13)
+    codes = rng.integers(0, 256, size=n_elems // 2, dtype=np.uint8)
+    absmax = ((0.5 + rng.random(n_elems // 64)) * (1.8 / np.sqrt(d_in))).astype(np.float32)
+    return codes, absmax
