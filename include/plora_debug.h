@@ -38,6 +38,8 @@
  *            records describe the first two; n_ext = the sum of rp / 64 over such segments
  *   blk_seg[n_blocks] int32: segment of each 128-row token block
  *   seg_list int32: the non-empty segments with an adapter, grouped by adapter, in segment order
+ *   tile_order[n_tiles] int32: the 256-row tiles in the order the base GEMMs walk them, sorted by min(n_ext, 8),
+ *            largest first, tiles of equal class in row order (tiles that run side by side are then equally long)
  */
 #ifndef PLORA_DEBUG_H
 #define PLORA_DEBUG_H
@@ -59,6 +61,7 @@ typedef struct {
     /* byte offsets of the workspace regions */
     uint64_t ws_zero, ws_meta, ws_desc, ws_at, ws_ap, ws_hb, ws_zt_h, ws_zt_g, ws_hf, ws_gf, ws_part, ws_wpart, ws_total;
     uint64_t h_elems;
+    uint64_t off_tile_order;
 } plora_debug_info;
 
 /* Fills *info and, if tables_out is not NULL, copies the table image (info->table_bytes bytes;

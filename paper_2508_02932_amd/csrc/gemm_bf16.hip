@@ -96,7 +96,8 @@ __device__ inline void wait_vmcnt_048(int n)
 }
 
 template <bool FWD>
-__global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles, const SegInfo *__restrict__ segs,
+__global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles, const int32_t *__restrict__ order,
+                                              const SegInfo *__restrict__ segs,
                                               const AdapterInfo *__restrict__ ads, const uint16_t *__restrict__ S,
                                               const uint16_t *__restrict__ W, const uint16_t *__restrict__ side,
                                               const uint16_t *__restrict__ ap, const uint16_t *__restrict__ zero,
@@ -107,6 +108,7 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
     // the scalar cache (a vector load would be counted, in order, with the direct-to-LDS loads of the ring)
     MetaView mv;
     mv.hdr = nullptr; mv.seg = segs; mv.ad = ads; mv.tile = tiles; mv.blk_seg = nullptr; mv.seg_list = nullptr;
+    mv.tile_order = order;
     // shapes come as kernel arguments, so the first loads do not wait for a metadata fetch.  FWD names the form of
     // the weight operand: W[Kd][N] (contraction index = row index; the forward product when W is [d_in][d_out]),
     // otherwise W[N][Kd]
@@ -115,7 +117,11 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
     // ---- workgroup -> tiles.  The grid is persistent (one workgroup per compute unit, each walks the
     // tile ids b, b + grid, b + 2 grid, ...).  Workgroups are dealt round-robin to the 8 XCDs (each with
     // its own L2); give every XCD a contiguous range of tile ids, and walk tile ids in groups of 4 row
-    // tiles so that the tiles resident on one XCD at a time share rows of S and columns of W.
+    // tiles so that the tiles resident on one XCD at a time share rows of S and columns of W.  The
+    // row tiles are taken in the order of the `order` table (sorted by their number of extension
+    // steps), so that the four row tiles of a group are equally long: workgroups that stream the same
+    // columns of W then stay in step, which is what makes that sharing work (tiles of unequal length
+    // side by side cost about 5 % of the kernel's time).
     const int n_tiles = tiles_m * tiles_n;
     int m0 = 0, n0 = 0, m1 = 0;
     auto tile_coords = [&](int vb, int &row_tile, int &col_tile) {
@@ -126,7 +132,7 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
         const int group = tile / (GM * tiles_n), first = group * GM;
         const int gsz = (tiles_m - first < GM) ? tiles_m - first : GM;
         const int in = tile - group * GM * tiles_n;
-        row_tile = first + in % gsz;
+        row_tile = order[first + in % gsz];
         col_tile = in / gsz;
     };
     auto set_tile = [&](int vb) {
@@ -539,7 +545,8 @@ static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, int64_
     const int n_cu = device_cu_count(&cu_err);
     if (n_cu < 1) return cu_err;
     const int n_tiles = tiles_m * tiles_n;
-    hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < n_cu ? n_tiles : n_cu)), dim3(512), kGemmLds, st, mv.tile, mv.seg, mv.ad,
+    hipLaunchKernelGGL(kern, dim3((unsigned)(n_tiles < n_cu ? n_tiles : n_cu)), dim3(512), kGemmLds, st, mv.tile, mv.tile_order,
+                       mv.seg, mv.ad,
                        static_cast<const uint16_t *>(S), static_cast<const uint16_t *>(W),
                        static_cast<const uint16_t *>(side), static_cast<const uint16_t *>(ap),
                        static_cast<const uint16_t *>(zero), static_cast<uint16_t *>(C), tiles_m, tiles_n, (int)h.T, (int)Kd,

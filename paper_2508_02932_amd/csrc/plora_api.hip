@@ -103,6 +103,12 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     const DescReader<WordsInMemory> in{WordsInMemory{words.data()}};
     derive_phase1(in, m.t);
     derive_phase2(m.t, 0, 1);
+    {
+        int32_t counts[kSortKeys], starts[kSortKeys];
+        derive_phase3_count(m.t, 0, 1, counts);
+        derive_phase3_scan(0, 1, counts, starts);
+        derive_phase3_place(m.t, 0, 1, starts);
+    }
     m.hdr = *m.t.hdr;
 
     int64_t h = 0, hb = 0, zt = 0, at = 0, ap = 0;
@@ -524,6 +530,7 @@ int plora_debug_metadata(const plora_desc *desc, plora_debug_info *info, void *t
         info->tile_stride = (int32_t)sizeof(GemmTile);
         info->off_hdr = m.layout.hdr; info->off_seg = m.layout.seg; info->off_ad = m.layout.ad;
         info->off_tile = m.layout.tile; info->off_blk_seg = m.layout.blk_seg; info->off_seg_list = m.layout.seg_list;
+        info->off_tile_order = m.layout.tile_order;
         info->table_bytes = m.layout.bytes;
         info->shrink_splits = m.split_shrink; info->dh_splits = m.split_dh;
         info->da_splits = m.split_dA; info->da_tile_cols = m.bc_dA;

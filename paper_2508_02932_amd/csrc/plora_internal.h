@@ -106,6 +106,7 @@ struct MetaView {
     const GemmTile *tile;     // one per 256-row tile
     const int32_t *blk_seg;   // segment of each token block of kSkinnyRows rows
     const int32_t *seg_list;  // non-empty segments grouped by adapter (see AdapterInfo)
+    const int32_t *tile_order;  // the GEMM row tiles ordered by extension steps, most first (ties: lower tile first)
 };
 
 // ---- compact description -----------------------------------------------------------------------
@@ -156,7 +157,7 @@ PLORA_HD size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Byte offsets of the derived tables inside the metadata region of the workspace.
 struct TableLayout {
-    size_t hdr, seg, ad, tile, blk_seg, seg_list, bytes;
+    size_t hdr, seg, ad, tile, blk_seg, seg_list, tile_order, bytes;
     int64_t n_tiles;
 };
 
@@ -171,6 +172,7 @@ PLORA_HD TableLayout table_layout(int64_t T, int n_seg, int n_adapters, int n_bl
     l.tile = o;     o = align_up(o + (size_t)l.n_tiles * sizeof(GemmTile), 64);
     l.blk_seg = o;  o = align_up(o + (size_t)n_blocks * sizeof(int32_t), 64);
     l.seg_list = o; o = align_up(o + (size_t)n_seg * sizeof(int32_t), 64);
+    l.tile_order = o; o = align_up(o + (size_t)l.n_tiles * sizeof(int32_t), 64);
     l.bytes = o;
     return l;
 }
@@ -183,6 +185,7 @@ struct Tables {
     GemmTile *tile;
     int32_t *blk_seg;
     int32_t *seg_list;
+    int32_t *tile_order;
 };
 
 PLORA_HD Tables tables_at(char *base, const TableLayout &l)
@@ -194,13 +197,14 @@ PLORA_HD Tables tables_at(char *base, const TableLayout &l)
     t.tile = reinterpret_cast<GemmTile *>(base + l.tile);
     t.blk_seg = reinterpret_cast<int32_t *>(base + l.blk_seg);
     t.seg_list = reinterpret_cast<int32_t *>(base + l.seg_list);
+    t.tile_order = reinterpret_cast<int32_t *>(base + l.tile_order);
     return t;
 }
 
 PLORA_HD MetaView view_of(const Tables &t)
 {
     MetaView v;
-    v.hdr = t.hdr; v.seg = t.seg; v.ad = t.ad; v.tile = t.tile; v.blk_seg = t.blk_seg; v.seg_list = t.seg_list;
+    v.hdr = t.hdr; v.seg = t.seg; v.ad = t.ad; v.tile = t.tile; v.blk_seg = t.blk_seg; v.seg_list = t.seg_list; v.tile_order = t.tile_order;
     return v;
 }
 
@@ -339,6 +343,59 @@ PLORA_HD void derive_phase2(const Tables &t, int tid, int nthreads)
         }
         t.ad[rank].by_tokens = k;
     }
+}
+
+// Phase 3 (after phase 2): the order in which the GEMMs walk their row tiles.  Workgroups that run side by side
+// on one XCD work on a group of kGemmGroupRows consecutive entries of this order and share the columns of W they
+// stream; they only stay in step if their tiles have the same number of contraction steps, so the row tiles are
+// sorted by their extension steps, most first, tiles of equal length in row order (lengths of kSortKeys - 1 steps
+// and more count as one class).  A counting sort in three steps with a barrier between them: every thread counts
+// the classes in its own contiguous chunk of tiles, one thread per class turns the counts into start positions,
+// every thread places its chunk.  counts: kSortKeys ints per thread (device: LDS; host: one thread).
+constexpr int kSortKeys = 9;
+
+PLORA_HD int sort_key(int32_t n_ext) { return n_ext < kSortKeys - 1 ? n_ext : kSortKeys - 1; }
+
+PLORA_HD void tile_chunk(int64_t n_tiles, int tid, int nthreads, int64_t &lo, int64_t &hi)
+{
+    const int64_t per = (n_tiles + nthreads - 1) / nthreads;
+    lo = per * tid < n_tiles ? per * tid : n_tiles;
+    hi = lo + per < n_tiles ? lo + per : n_tiles;
+}
+
+PLORA_HD void derive_phase3_count(const Tables &t, int tid, int nthreads, int32_t *counts)
+{
+    const int64_t n_tiles = (t.hdr->T + kGemmTileRows - 1) / kGemmTileRows;
+    int64_t lo, hi;
+    tile_chunk(n_tiles, tid, nthreads, lo, hi);
+    int32_t c[kSortKeys];
+    for (int k = 0; k < kSortKeys; ++k) c[k] = 0;
+    for (int64_t i = lo; i < hi; ++i) c[sort_key(t.tile[i].n_ext)] += 1;
+    for (int k = 0; k < kSortKeys; ++k) counts[tid * kSortKeys + k] = c[k];
+}
+
+// counts[thread][class] -> starts[thread][class]: position of the first tile of that class in that thread's chunk
+PLORA_HD void derive_phase3_scan(int tid, int nthreads, const int32_t *counts, int32_t *starts)
+{
+    for (int k = tid; k < kSortKeys; k += nthreads) {       // one thread per class
+        int32_t base = 0;
+        for (int kk = kSortKeys - 1; kk > k; --kk)          // all tiles of the longer classes come first
+            for (int th = 0; th < nthreads; ++th) base += counts[th * kSortKeys + kk];
+        for (int th = 0; th < nthreads; ++th) {
+            starts[th * kSortKeys + k] = base;
+            base += counts[th * kSortKeys + k];
+        }
+    }
+}
+
+PLORA_HD void derive_phase3_place(const Tables &t, int tid, int nthreads, const int32_t *starts)
+{
+    const int64_t n_tiles = (t.hdr->T + kGemmTileRows - 1) / kGemmTileRows;
+    int64_t lo, hi;
+    tile_chunk(n_tiles, tid, nthreads, lo, hi);
+    int32_t pos[kSortKeys];
+    for (int k = 0; k < kSortKeys; ++k) pos[k] = starts[tid * kSortKeys + k];
+    for (int64_t i = lo; i < hi; ++i) t.tile_order[pos[sort_key(t.tile[i].n_ext)]++] = (int32_t)i;
 }
 
 // Byte offsets of the workspace regions, each 256-byte aligned.

@@ -189,7 +189,7 @@ struct WordsInArg {
 template <class Src>
 __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint32_t *zero_page, uint16_t *at, uint16_t *ap,
                                  int want_at, int want_ap, int pack_bx, int n_pack, int pack_bx_b, int n_pack_b,
-                                 const float *hf, uint16_t *zt, void *shared_mem)
+                                 const float *hf, uint16_t *zt, void *shared_mem, int32_t *sort_counts, int32_t *sort_starts)
 {
     int b = blockIdx.x;
     if (b == 0) {
@@ -200,6 +200,13 @@ __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint
         __threadfence_block();
         __syncthreads();
         derive_phase2(t, (int)threadIdx.x, 256);
+        __threadfence_block();
+        __syncthreads();
+        derive_phase3_count(t, (int)threadIdx.x, 256, sort_counts);
+        __syncthreads();
+        derive_phase3_scan((int)threadIdx.x, 256, sort_counts, sort_starts);
+        __syncthreads();
+        derive_phase3_place(t, (int)threadIdx.x, 256, sort_starts);
         return;
     }
     b -= 1;
@@ -273,8 +280,10 @@ __global__ void __launch_bounds__(256) k_prep_arg(DescChunk c, char *meta_dst, u
                                                  int n_pack_b, const float *hf, uint16_t *zt)
 {
     __shared__ __attribute__((aligned(16))) PrepShared sh;
+    __shared__ int32_t sort_counts[256 * kSortKeys], sort_starts[256 * kSortKeys];
     const DescReader<WordsInArg> in{WordsInArg{c}};
-    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, pack_bx_b, n_pack_b, hf, zt, &sh);
+    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, pack_bx_b, n_pack_b, hf, zt, &sh, sort_counts,
+              sort_starts);
 }
 
 __global__ void __launch_bounds__(256) k_prep_mem(const uint32_t *desc, char *meta_dst, uint32_t *zero_page, uint16_t *at,
@@ -282,8 +291,10 @@ __global__ void __launch_bounds__(256) k_prep_mem(const uint32_t *desc, char *me
                                                  int pack_bx_b, int n_pack_b, const float *hf, uint16_t *zt)
 {
     __shared__ __attribute__((aligned(16))) PrepShared sh;
+    __shared__ int32_t sort_counts[256 * kSortKeys], sort_starts[256 * kSortKeys];
     const DescReader<WordsInMemory> in{WordsInMemory{desc}};
-    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, pack_bx_b, n_pack_b, hf, zt, &sh);
+    prep_body(in, meta_dst, zero_page, at, ap, want_at, want_ap, pack_bx, n_pack, pack_bx_b, n_pack_b, hf, zt, &sh, sort_counts,
+              sort_starts);
 }
 
 hipError_t launch_prep(const uint32_t *desc_host, int n_words, const MetaHeader &h, char *meta_dev, uint32_t *desc_stage,

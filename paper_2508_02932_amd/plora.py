@@ -61,7 +61,8 @@ class plora_debug_info(C.Structure):
                 + [(n, C.c_int32) for n in ("shrink_splits", "dh_splits", "da_splits", "da_tile_cols", "db_splits",
                                             "db_tile_cols", "r16_total", "n_active")]
                 + [(n, C.c_uint64) for n in ("ws_zero", "ws_meta", "ws_desc", "ws_at", "ws_ap", "ws_hb", "ws_zt_h",
-                                             "ws_zt_g", "ws_hf", "ws_gf", "ws_part", "ws_wpart", "ws_total", "h_elems")])
+                                             "ws_zt_g", "ws_hf", "ws_gf", "ws_part", "ws_wpart", "ws_total", "h_elems",
+                                             "off_tile_order")])
 
 
 # numpy views of the records of the table image (include/plora_debug.h)
@@ -205,6 +206,7 @@ def parse_tables(info: plora_debug_info, image: np.ndarray) -> dict:
             "blk_seg": take(info.off_blk_seg, "<i4", info.n_blocks)}
     n_list = int(tabs["ad"]["n_own"].sum()) if info.n_adapters else 0
     tabs["seg_list"] = take(info.off_seg_list, "<i4", n_list)
+    tabs["tile_order"] = take(info.off_tile_order, "<i4", info.n_tiles)
     return tabs
 
 

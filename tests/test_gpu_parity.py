@@ -277,7 +277,7 @@ def _device_tables_equal_export(lin, w_layout=0):
     tabs["tile"]["s"]["B"] = 0
     got["hdr"]["at_base"] = 0
     assert got["hdr"] == tabs["hdr"]
-    for name in ("seg", "ad", "tile", "blk_seg", "seg_list"):
+    for name in ("seg", "ad", "tile", "blk_seg", "seg_list", "tile_order"):
         assert np.array_equal(got[name], tabs[name]), name
     return dp
 

@@ -96,6 +96,9 @@ def check(T, D, K, seg_off, seg_adapter, rank, scale, w_layout=0):
             assert (int(q["row0"]), int(q["row1"]), int(q["rp"]), int(q["r"]), int(q["hb_off"]), int(q["ap_off"])) == \
                 (seg[s]["row0"], seg[s]["row1"], seg[s]["rp"], seg[s]["r"], seg[s]["hb_off"], ad[seg_adapter[s]]["ap_off"])
             assert int(q["B"]) == (2 * ad[seg_adapter[s]]["at_off"] if w_layout else 0)
+    # the order the GEMMs walk the row tiles in: longest extension first (8 steps and more are one class), ties in row order
+    want_order = sorted(range(len(tiles)), key=lambda i: (-min(tiles[i]["n_ext"], 8), i))
+    assert tabs["tile_order"].tolist() == want_order
     # launch plans and workspace: ranges and sizes
     for v in (info.shrink_splits, info.dh_splits, info.da_splits, info.db_splits):
         assert 1 <= v <= 8
