@@ -324,10 +324,10 @@ static hipError_t launch_tokc(const MetaView &mv, const MetaHeader &h, const uin
                               const uint16_t *zero, float *part, int n_split, int r16_total, hipStream_t st)
 {
     // ring depth: the share of the 160 KB of LDS that lets 256 / BC workgroups sit on a compute unit,
-    // but three stages at least
+    // but two stages at least (a second workgroup on the compute unit pays more than a third stage: measured)
     const size_t stage = (size_t)TC_BT * BC * 2 + (size_t)(h.max_r16 > 0 ? h.max_r16 : 16) * TC_BT * 2;
     size_t budget = (size_t)TC_LDS_BYTES * BC / 256;
-    if (budget < 3 * stage) budget = 3 * stage;
+    if (budget < 2 * stage) budget = 2 * stage;
     int nst = (int)(budget / stage);
     nst = nst > TC_MAX_NST ? TC_MAX_NST : nst;
     const size_t lds = nst * stage;
