@@ -101,7 +101,8 @@ static void build_meta(const plora_desc *d, HostMeta &m)
     m.image.assign(m.layout.bytes, 0);
     m.t = tables_at(m.image.data(), m.layout);
     const DescReader<WordsInMemory> in{WordsInMemory{words.data()}};
-    derive_phase1(in, m.t);
+    std::vector<int32_t> scratch(3 * (size_t)d->n_adapters + 1);
+    derive_phase1(in, m.t, scratch.data());
     derive_phase2(m.t, 0, 1);
     {
         int32_t counts[kSortKeys], starts[kSortKeys];

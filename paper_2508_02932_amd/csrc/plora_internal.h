@@ -213,30 +213,16 @@ PLORA_HD MetaView view_of(const Tables &t)
 // "for (i = tid; i < n; i += nthreads)" over independent entries.  Phase 2 reads what phase 1 wrote, so
 // the caller separates them with a barrier (device: one workgroup, __syncthreads; host: tid 0 of 1, nothing to do).
 
-template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, const Tables &t)
+// scratch: 3 ints per adapter (tokens, non-empty segments, list cursor).  On the device it lies in LDS: the one
+// thread that runs this phase then never waits for a load from memory - everything it reads comes from the
+// description or from the scratch, everything it writes to the tables is a store it does not wait for.
+template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, const Tables &t, int32_t *scratch)
 {
     const int n_seg = in.n_seg(), n_ad = in.n_adapters();
     const int64_t D = in.D();
     const int64_t ap_rows = in.w_out_in() ? in.K() : D;   // rows of the padded operand [rows][rp], see GemmSeg
-    int64_t at = 0, ap = 0;
-    int32_t r16_off = 0;
-    for (int k = 0; k < n_ad; ++k) {
-        AdapterInfo a;
-        a.A = in.ad_ptr(k, 0);
-        a.B = in.ad_ptr(k, 1);
-        a.dA = static_cast<float *>(const_cast<void *>(in.ad_ptr(k, 2)));
-        a.dB = static_cast<float *>(const_cast<void *>(in.ad_ptr(k, 3)));
-        a.r = in.ad_rank(k);
-        a.rp = pad_to(a.r, kRankPadGemm);
-        a.r16 = pad_to(a.r, kRankPadMfma);
-        a.scale = in.ad_scale(k);
-        a.at_off = at; at += (int64_t)a.r16 * D;
-        a.ext_b = in.w_out_in() ? static_cast<const void *>(static_cast<const char *>(in.at_base()) + 2 * a.at_off) : a.B;
-        a.ap_off = ap; ap += (int64_t)a.rp * ap_rows;
-        a.r16_off = r16_off; r16_off += a.r16;
-        a.by_tokens = 0; a.seg_list0 = 0; a.n_own = 0; a.tokens = 0; a.reserved = 0;
-        t.ad[k] = a;
-    }
+    int32_t *tokens = scratch, *n_own = scratch + n_ad, *cursor = scratch + 2 * n_ad;
+    for (int k = 0; k < n_ad; ++k) { tokens[k] = 0; n_own[k] = 0; }
     int64_t h = 0, hb = 0, zt = 0;
     int32_t blk = 0, max_r16 = 0, row0 = 0;
     for (int s = 0; s < n_seg; ++s) {
@@ -257,19 +243,41 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
             h += (int64_t)len * g.r;
             hb += (int64_t)len * g.rp;
             zt += (int64_t)g.r16 * g.lp;
-            t.ad[g.adapter].tokens += len;
-            t.ad[g.adapter].n_own += len > 0;
+            tokens[g.adapter] += len;
+            n_own[g.adapter] += len > 0;
         }
         t.seg[s] = g;
     }
-    // per-adapter lists of non-empty segments, in segment order
-    int32_t o = 0;
-    for (int k = 0; k < n_ad; ++k) { t.ad[k].seg_list0 = o; t.ad[k].reserved = o; o += t.ad[k].n_own; }
-    for (int s = 0; s < n_seg; ++s) {
-        const int a = t.seg[s].adapter;
-        if (a >= 0 && t.seg[s].row1 > t.seg[s].row0) t.seg_list[t.ad[a].reserved++] = s;
+    int64_t at = 0, ap = 0;
+    int32_t r16_off = 0, list0 = 0;
+    for (int k = 0; k < n_ad; ++k) {
+        AdapterInfo a;
+        a.A = in.ad_ptr(k, 0);
+        a.B = in.ad_ptr(k, 1);
+        a.dA = static_cast<float *>(const_cast<void *>(in.ad_ptr(k, 2)));
+        a.dB = static_cast<float *>(const_cast<void *>(in.ad_ptr(k, 3)));
+        a.r = in.ad_rank(k);
+        a.rp = pad_to(a.r, kRankPadGemm);
+        a.r16 = pad_to(a.r, kRankPadMfma);
+        a.scale = in.ad_scale(k);
+        a.at_off = at; at += (int64_t)a.r16 * D;
+        a.ext_b = in.w_out_in() ? static_cast<const void *>(static_cast<const char *>(in.at_base()) + 2 * a.at_off) : a.B;
+        a.ap_off = ap; ap += (int64_t)a.rp * ap_rows;
+        a.r16_off = r16_off; r16_off += a.r16;
+        a.by_tokens = 0;                    // filled in by phase 2
+        a.seg_list0 = list0; a.n_own = n_own[k]; a.tokens = tokens[k]; a.reserved = 0;
+        cursor[k] = list0;
+        list0 += n_own[k];
+        t.ad[k] = a;
     }
-    for (int k = 0; k < n_ad; ++k) t.ad[k].reserved = 0;
+    // per-adapter lists of non-empty segments, in segment order
+    int32_t prev = 0;
+    for (int s = 0; s < n_seg; ++s) {
+        const int32_t row1 = in.seg_row1(s);
+        const int a = in.seg_adapter(s);
+        if (a >= 0 && row1 > prev) t.seg_list[cursor[a]++] = s;
+        prev = row1;
+    }
     MetaHeader hd;
     hd.T = in.T(); hd.D = D; hd.K = in.K();
     hd.n_seg = n_seg; hd.n_adapters = n_ad; hd.n_blocks = blk; hd.max_r16 = max_r16;

@@ -196,7 +196,7 @@ __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint
         zero_page[threadIdx.x] = 0u;     // kZeroBytes = 256 * 4
         const TableLayout lay = table_layout(in.T(), in.n_seg(), in.n_adapters(), in.n_blocks());
         const Tables t = tables_at(meta_dst, lay);
-        if (threadIdx.x == 0) derive_phase1(in, t);
+        if (threadIdx.x == 0) derive_phase1(in, t, sort_counts);   // the sort's counters are free until phase 3
         __threadfence_block();
         __syncthreads();
         derive_phase2(t, (int)threadIdx.x, 256);
