@@ -51,12 +51,12 @@ static plora_status validate(const plora_desc *d)
 // Compact description of a call (the words the preparation kernel receives).  Pointer tables may be null.
 // at_base: device address of the packed-A^T region of the workspace (null when only the layout matters).
 static void fill_desc_words(const plora_desc *d, int32_t n_blocks, const void *const *A, const void *const *B,
-                            float *const *dA, float *const *dB, const void *at_base, uint32_t *w)
+                            float *const *dA, float *const *dB, const void *at_base, bool order_is_identity, uint32_t *w)
 {
     auto put64 = [&](int i, uint64_t v) { w[i] = (uint32_t)v; w[i + 1] = (uint32_t)(v >> 32); };
     put64(0, (uint64_t)d->T); put64(2, (uint64_t)d->d_in); put64(4, (uint64_t)d->d_out);
     w[6] = (uint32_t)d->n_seg; w[7] = (uint32_t)d->n_adapters; w[8] = (uint32_t)n_blocks;
-    w[9] = d->w_layout == PLORA_W_OUT_IN ? 1u : 0u;
+    w[9] = (d->w_layout == PLORA_W_OUT_IN ? 1u : 0u) | (order_is_identity ? 2u : 0u);
     put64(10, (uint64_t)(uintptr_t)at_base);
     uint32_t *p = w + kDescHeadWords;
     for (int32_t s = 0; s < d->n_seg; ++s) { *p++ = (uint32_t)d->seg_off[s + 1]; *p++ = (uint32_t)d->seg_adapter[s]; }
@@ -87,6 +87,7 @@ struct HostMeta {
     int r16_total = 0, n_active = 0, split_dA = 1, split_dB = 1, bc_dA = 256, bc_dB = 256;
     int split_shrink = 1, split_dh = 1;
     int n_words = 0;
+    bool order_is_identity = false;   // the sorted order of the GEMM row tiles is 0, 1, 2, ...: the device need not sort
 };
 
 static void build_meta(const plora_desc *d, HostMeta &m)
@@ -96,20 +97,22 @@ static void build_meta(const plora_desc *d, HostMeta &m)
         if (d->seg_adapter[s] >= 0) n_blocks += (d->seg_off[s + 1] - d->seg_off[s] + kSkinnyRows - 1) / kSkinnyRows;
     m.n_words = desc_words(d->n_seg, d->n_adapters);
     std::vector<uint32_t> words((size_t)m.n_words);
-    fill_desc_words(d, n_blocks, nullptr, nullptr, nullptr, nullptr, nullptr, words.data());
+    fill_desc_words(d, n_blocks, nullptr, nullptr, nullptr, nullptr, nullptr, false, words.data());
     m.layout = table_layout(d->T, d->n_seg, d->n_adapters, n_blocks);
     m.image.assign(m.layout.bytes, 0);
     m.t = tables_at(m.image.data(), m.layout);
     const DescReader<WordsInMemory> in{WordsInMemory{words.data()}};
     std::vector<int32_t> scratch(3 * (size_t)d->n_adapters + 1);
-    derive_phase1(in, m.t, scratch.data());
-    derive_phase2(m.t, 0, 1);
+    derive_phase1(in, m.t, scratch.data(), nullptr, nullptr, nullptr);
+    derive_phase2(m.t, *m.t.hdr, m.t.seg, m.t.ad, scratch.data() /* tokens */, 0, 1);
     {
         int32_t counts[kSortKeys], starts[kSortKeys];
-        derive_phase3_count(m.t, 0, 1, counts);
+        derive_phase3_count(m.t, m.layout.n_tiles, 0, 1, counts);
         derive_phase3_scan(0, 1, counts, starts);
-        derive_phase3_place(m.t, 0, 1, starts);
+        derive_phase3_place(m.t, m.layout.n_tiles, 0, 1, starts);
     }
+    m.order_is_identity = true;
+    for (int64_t i = 0; i < m.layout.n_tiles; ++i) m.order_is_identity = m.order_is_identity && m.t.tile_order[i] == (int32_t)i;
     m.hdr = *m.t.hdr;
 
     int64_t h = 0, hb = 0, zt = 0, at = 0, ap = 0;
@@ -263,7 +266,7 @@ static plora_status prepare(const plora_desc *d, const void *x, const void *W, c
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
     uint32_t *w = c.small;
     if (c.m->n_words > kChunkWords) { c.large.resize((size_t)c.m->n_words); w = c.large.data(); }
-    fill_desc_words(d, c.m->hdr.n_blocks, A, B, dA, dB, static_cast<const char *>(workspace) + c.L->at, w);
+    fill_desc_words(d, c.m->hdr.n_blocks, A, B, dA, dB, static_cast<const char *>(workspace) + c.L->at, c.m->order_is_identity, w);
     c.words = w;
     return PLORA_OK;
 }

@@ -111,7 +111,8 @@ struct MetaView {
 
 // ---- compact description -----------------------------------------------------------------------
 // 32-bit words: [0,1] T  [2,3] D  [4,5] K  [6] n_seg  [7] n_adapters  [8] n_blocks (computed by the host, fixes the
-// table layout)  [9] 1 if W is stored [d_out][d_in]  [10,11] device address of the packed-A^T buffer; then per segment
+// table layout)  [9] bit 0: W is stored [d_out][d_in], bit 1: the sorted order of the GEMM row tiles is the identity (the
+// host knows from its own derivation; the device then skips the sort)  [10,11] device address of the packed-A^T buffer; then per segment
 // {row1, adapter}; then per adapter {A lo, A hi, B lo, B hi, dA lo, dA hi, dB lo, dB hi, r, scale bits}.
 constexpr int kDescHeadWords = 12, kDescSegWords = 2, kDescAdWords = 10;
 constexpr int kChunkWords = 896;   // 3584 bytes: what one launch carries by value, below the 4 KB kernel-argument limit
@@ -136,7 +137,8 @@ template <class Src> struct DescReader {
     PLORA_HD int n_seg() const { return (int)src.word(6); }
     PLORA_HD int n_adapters() const { return (int)src.word(7); }
     PLORA_HD int n_blocks() const { return (int)src.word(8); }
-    PLORA_HD int w_out_in() const { return (int)src.word(9); }
+    PLORA_HD int w_out_in() const { return (int)(src.word(9) & 1u); }
+    PLORA_HD int order_is_identity() const { return (int)((src.word(9) >> 1) & 1u); }
     PLORA_HD const void *at_base() const { return reinterpret_cast<const void *>((uintptr_t)w64(10)); }
     PLORA_HD int seg_row1(int s) const { return (int)src.word(kDescHeadWords + kDescSegWords * s); }
     PLORA_HD int seg_row0(int s) const { return s ? seg_row1(s - 1) : 0; }
@@ -216,7 +218,16 @@ PLORA_HD MetaView view_of(const Tables &t)
 // scratch: 3 ints per adapter (tokens, non-empty segments, list cursor).  On the device it lies in LDS: the one
 // thread that runs this phase then never waits for a load from memory - everything it reads comes from the
 // description or from the scratch, everything it writes to the tables is a store it does not wait for.
-template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, const Tables &t, int32_t *scratch)
+// seg_copy / ad_copy (either may be null): a second place for the segment records and for what the tile records need
+// of an adapter.  On the device they lie in LDS, so that the phases that follow read them from there and not from the
+// tables in memory (every such read would be a trip to the L2, and the tile derivation chains several).
+struct AdapterGemm {
+    const void *ext_b;
+    int64_t ap_off;
+};
+
+template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, const Tables &t, int32_t *scratch,
+                                                 SegInfo *seg_copy, AdapterGemm *ad_copy, MetaHeader *hd_copy)
 {
     const int n_seg = in.n_seg(), n_ad = in.n_adapters();
     const int64_t D = in.D();
@@ -247,6 +258,7 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
             n_own[g.adapter] += len > 0;
         }
         t.seg[s] = g;
+        if (seg_copy) seg_copy[s] = g;
     }
     int64_t at = 0, ap = 0;
     int32_t r16_off = 0, list0 = 0;
@@ -269,6 +281,7 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
         cursor[k] = list0;
         list0 += n_own[k];
         t.ad[k] = a;
+        if (ad_copy) { ad_copy[k].ext_b = a.ext_b; ad_copy[k].ap_off = a.ap_off; }
     }
     // per-adapter lists of non-empty segments, in segment order
     int32_t prev = 0;
@@ -283,6 +296,7 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
     hd.n_seg = n_seg; hd.n_adapters = n_ad; hd.n_blocks = blk; hd.max_r16 = max_r16;
     hd.w_out_in = in.w_out_in(); hd.reserved = 0; hd.at_base = in.at_base();
     *t.hdr = hd;
+    if (hd_copy) *hd_copy = hd;
 }
 
 PLORA_HD bool seg_has_lowrank(const SegInfo &g) { return g.adapter >= 0 && g.row1 > g.row0; }
@@ -300,15 +314,17 @@ PLORA_HD int seg_of_block(const SegInfo *seg, int n_seg, int blk)
     return lo;
 }
 
-// Extension steps and the first segments of one GEMM row tile.
-PLORA_HD void derive_tile(const Tables &t, int n_seg, int64_t T, int64_t tile)
+// Extension steps and the first segments of one GEMM row tile.  seg / ad: where to read the segment records and the
+// adapters' GEMM operands from (the tables themselves, or the copies phase 1 made).
+template <class AdSrc>
+PLORA_HD void derive_tile(const Tables &t, const SegInfo *seg, const AdSrc *ad, int n_seg, int64_t T, int64_t tile)
 {
     const int64_t m0 = tile * kGemmTileRows;
     const int64_t m1 = m0 + kGemmTileRows < T ? m0 + kGemmTileRows : T;
     int lo = 0, hi = n_seg;                     // first segment with row1 > m0
     while (lo < hi) {
         const int mid = (lo + hi) / 2;
-        if (t.seg[mid].row1 > m0) hi = mid; else lo = mid + 1;
+        if (seg[mid].row1 > m0) hi = mid; else lo = mid + 1;
     }
     GemmTile gt;
     gt.n_ext = 0; gt.n_own = 0; gt.first_seg = n_seg; gt.third_seg = n_seg;
@@ -316,13 +332,13 @@ PLORA_HD void derive_tile(const Tables &t, int n_seg, int64_t T, int64_t tile)
         gt.s[i].row0 = 0; gt.s[i].row1 = 0; gt.s[i].rp = 0; gt.s[i].r = 0;
         gt.s[i].hb_off = 0; gt.s[i].B = nullptr; gt.s[i].ap_off = 0;
     }
-    for (int s = lo; s < n_seg && t.seg[s].row0 < m1; ++s) {
-        const SegInfo &g = t.seg[s];
+    for (int s = lo; s < n_seg && seg[s].row0 < m1; ++s) {
+        const SegInfo g = seg[s];
         if (!seg_has_lowrank(g)) continue;
         if (gt.n_own < 2) {
             GemmSeg &q = gt.s[gt.n_own];
             q.row0 = g.row0; q.row1 = g.row1; q.rp = g.rp; q.r = g.r; q.hb_off = g.hb_off;
-            q.B = t.ad[g.adapter].ext_b; q.ap_off = t.ad[g.adapter].ap_off;
+            q.B = ad[g.adapter].ext_b; q.ap_off = ad[g.adapter].ap_off;
             if (gt.n_own == 0) gt.first_seg = s;
         } else if (gt.n_own == 2) {
             gt.third_seg = s;
@@ -333,20 +349,24 @@ PLORA_HD void derive_tile(const Tables &t, int n_seg, int64_t T, int64_t tile)
     t.tile[tile] = gt;
 }
 
-PLORA_HD void derive_phase2(const Tables &t, int tid, int nthreads)
+// hd: the header as phase 1 wrote it (passed by value so that nobody has to read it back); tokens: per-adapter token
+// counts (phase 1's scratch).
+template <class AdSrc>
+PLORA_HD void derive_phase2(const Tables &t, const MetaHeader &hd, const SegInfo *seg, const AdSrc *ad, const int32_t *tokens,
+                            int tid, int nthreads)
 {
-    const int n_seg = t.hdr->n_seg, n_ad = t.hdr->n_adapters, n_blocks = t.hdr->n_blocks;
-    const int64_t T = t.hdr->T;
+    const int n_seg = hd.n_seg, n_ad = hd.n_adapters, n_blocks = hd.n_blocks;
+    const int64_t T = hd.T;
     const int64_t n_tiles = (T + kGemmTileRows - 1) / kGemmTileRows;
-    for (int b = tid; b < n_blocks; b += nthreads) t.blk_seg[b] = seg_of_block(t.seg, n_seg, b);
-    for (int64_t tile = tid; tile < n_tiles; tile += nthreads) derive_tile(t, n_seg, T, tile);
+    for (int b = tid; b < n_blocks; b += nthreads) t.blk_seg[b] = seg_of_block(seg, n_seg, b);
+    for (int64_t tile = tid; tile < n_tiles; tile += nthreads) derive_tile(t, seg, ad, n_seg, T, tile);
     // place of each adapter in the order by token count, longest first (the weight-gradient kernels hand out
     // adapters in that order, so the last workgroups are short)
     for (int k = tid; k < n_ad; k += nthreads) {
-        const int32_t mine = t.ad[k].tokens;
+        const int32_t mine = tokens[k];
         int rank = 0;
         for (int j = 0; j < n_ad; ++j) {
-            const int32_t theirs = t.ad[j].tokens;
+            const int32_t theirs = tokens[j];
             if (theirs > mine || (theirs == mine && j < k)) ++rank;
         }
         t.ad[rank].by_tokens = k;
@@ -371,9 +391,8 @@ PLORA_HD void tile_chunk(int64_t n_tiles, int tid, int nthreads, int64_t &lo, in
     hi = lo + per < n_tiles ? lo + per : n_tiles;
 }
 
-PLORA_HD void derive_phase3_count(const Tables &t, int tid, int nthreads, int32_t *counts)
+PLORA_HD void derive_phase3_count(const Tables &t, int64_t n_tiles, int tid, int nthreads, int32_t *counts)
 {
-    const int64_t n_tiles = (t.hdr->T + kGemmTileRows - 1) / kGemmTileRows;
     int64_t lo, hi;
     tile_chunk(n_tiles, tid, nthreads, lo, hi);
     int32_t c[kSortKeys];
@@ -396,9 +415,8 @@ PLORA_HD void derive_phase3_scan(int tid, int nthreads, const int32_t *counts, i
     }
 }
 
-PLORA_HD void derive_phase3_place(const Tables &t, int tid, int nthreads, const int32_t *starts)
+PLORA_HD void derive_phase3_place(const Tables &t, int64_t n_tiles, int tid, int nthreads, const int32_t *starts)
 {
-    const int64_t n_tiles = (t.hdr->T + kGemmTileRows - 1) / kGemmTileRows;
     int64_t lo, hi;
     tile_chunk(n_tiles, tid, nthreads, lo, hi);
     int32_t pos[kSortKeys];

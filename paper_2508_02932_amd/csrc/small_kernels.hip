@@ -186,6 +186,8 @@ struct WordsInArg {
     __device__ inline uint32_t word(int i) const { return c.w[i]; }
 };
 
+constexpr int kPrepSegCopies = 64 * PLORA_MAX_RANK * 2 / (int)sizeof(SegInfo);   // segment records that fit the pack tile
+
 template <class Src>
 __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint32_t *zero_page, uint16_t *at, uint16_t *ap,
                                  int want_at, int want_ap, int pack_bx, int n_pack, int pack_bx_b, int n_pack_b,
@@ -196,17 +198,28 @@ __device__ inline void prep_body(const DescReader<Src> &in, char *meta_dst, uint
         zero_page[threadIdx.x] = 0u;     // kZeroBytes = 256 * 4
         const TableLayout lay = table_layout(in.T(), in.n_seg(), in.n_adapters(), in.n_blocks());
         const Tables t = tables_at(meta_dst, lay);
-        if (threadIdx.x == 0) derive_phase1(in, t, sort_counts);   // the sort's counters are free until phase 3
+        // LDS of this workgroup (it packs nothing): the pack tile holds a copy of the segment records when they fit,
+        // the second sort array the adapters' GEMM operands and the header; the first sort array is phase 1's scratch
+        SegInfo *seg_copy = in.n_seg() <= kPrepSegCopies ? static_cast<SegInfo *>(shared_mem) : nullptr;
+        AdapterGemm *ad_copy = reinterpret_cast<AdapterGemm *>(sort_starts);
+        MetaHeader *hd_copy = reinterpret_cast<MetaHeader *>(ad_copy + PLORA_MAX_ADAPTERS);
+        if (threadIdx.x == 0) derive_phase1(in, t, sort_counts, seg_copy, ad_copy, hd_copy);
         __threadfence_block();
         __syncthreads();
-        derive_phase2(t, (int)threadIdx.x, 256);
+        const MetaHeader hd = *hd_copy;
+        const int64_t n_tiles = (hd.T + kGemmTileRows - 1) / kGemmTileRows;
+        derive_phase2(t, hd, seg_copy ? seg_copy : t.seg, ad_copy, sort_counts /* tokens */, (int)threadIdx.x, 256);
+        if (in.order_is_identity()) {           // all row tiles equally long, or already in order: nothing to sort
+            for (int64_t i = threadIdx.x; i < n_tiles; i += 256) t.tile_order[i] = (int32_t)i;
+            return;
+        }
         __threadfence_block();
-        __syncthreads();
-        derive_phase3_count(t, (int)threadIdx.x, 256, sort_counts);
+        __syncthreads();                        // also: everybody is done with the token counts and the copies
+        derive_phase3_count(t, n_tiles, (int)threadIdx.x, 256, sort_counts);
         __syncthreads();
         derive_phase3_scan((int)threadIdx.x, 256, sort_counts, sort_starts);
         __syncthreads();
-        derive_phase3_place(t, (int)threadIdx.x, 256, sort_starts);
+        derive_phase3_place(t, n_tiles, (int)threadIdx.x, 256, sort_starts);
         return;
     }
     b -= 1;
