@@ -304,3 +304,33 @@ def test_many_adapters_chunked_description():
     assert info.desc_words > 896
     _device_tables_equal_export(lin)
     run_and_compare(lin)
+
+
+def test_most_adapters_and_segments():
+    """The largest description the interface takes: 256 adapters, 1024 segments (many of them empty or a few rows
+    long), so that the description travels in several chunks and the segment table no longer fits the preparation
+    kernel's LDS copy."""
+    from paper_2508_02932_amd import plora
+    import gpu_harness as gh
+    n_ad, n_seg = 256, 1024
+    rng = np.random.default_rng(19)
+    lengths = rng.integers(0, 12, size=n_seg)
+    lengths[rng.integers(0, n_seg, size=40)] = rng.integers(100, 400, size=40)      # some long enough for several blocks
+    seg_adapter = rng.integers(-1, n_ad, size=n_seg)
+    ranks = rng.integers(1, 129, size=n_ad)
+    lin = wl.small("most_adapters", "bf16", 72, 136, lengths=lengths.tolist(), seg_adapter=seg_adapter.tolist(),
+                   ranks=ranks.tolist(), scales=[0.5] * n_ad, seed=163)
+    info, _, _ = plora.plora_debug_metadata(gh.desc_of(lin))
+    assert info.desc_words > 3 * 896
+    _device_tables_equal_export(lin)
+    run_and_compare(lin, impl=oracle.matmul)
+
+
+def test_tall_batch():
+    """Several hundred thousand token rows against a narrow layer: thousands of GEMM row tiles and token blocks (the
+    tile order, the block table and every 64-bit row offset at a size the configurations never reach)."""
+    rng = np.random.default_rng(23)
+    lengths = [150_001, 0, 99_999, 250_000, 37, 100_003]
+    lin = wl.small("tall", "bf16", 16, 24, lengths=lengths, seg_adapter=[0, 1, 2, -1, 1, 0], ranks=[8, 128, 40],
+                   scales=[2.0, 1.0, 0.5], seed=167)
+    run_and_compare(lin, impl=oracle.matmul)
