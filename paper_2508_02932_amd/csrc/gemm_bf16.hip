@@ -421,6 +421,17 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
         asm volatile("" ::"s"(a), "s"(b));
     };
 
+    // Placement of the loops below in the instruction stream, fixed here so that it does not move when code above
+    // changes: a 256-byte boundary plus a few 4-byte no-ops.  The kernel's time depends on where its loops fall
+    // inside the 32-byte windows instructions are fetched in, by up to 10 % at the largest shapes (8192 -> 28672,
+    // 32768 tokens: 12.15 to 13.43 ms over the eight possible offsets for the first form, 11.50 to 12.33 ms for the
+    // second) and through a second-order effect: compute units that share an instruction cache fall a few cycles out
+    // of step with one another, and that decides whether the workgroups that stream the same rows of S and columns
+    // of W ask the L2 for a line one after the other (one miss, the rest hits) or at the same instant (every one a
+    // miss: 1.9e8 against 5.9e8 L2 misses per launch).  The offsets were chosen by measurement, one per form;
+    // any change to the code from here to the end of the kernel calls for a new sweep.
+    if (FWD) asm volatile(".p2align 8\n\ts_nop 0" ::: "memory");
+    else asm volatile(".p2align 8\n\ts_nop 0\n\ts_nop 0\n\ts_nop 0\n\ts_nop 0" ::: "memory");
     int vb = blockIdx.x;
     set_tile(vb);
     prologue();
