@@ -197,6 +197,29 @@ def main():
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) * 1e3 / steps
 
+    def graph_ms(step_fn, n_sets, reps=3):
+        """The same steps recorded once in a HIP graph (one step per input set) and replayed: ms per step without the
+        host's share of the launches."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            step_fn(0)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                for i in range(n_sets):
+                    step_fn(i)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            g.replay()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / (reps * n_sets)
+        del g
+        return ms
+
     def kernel_times(step_fn, steps):
         plora.plora_set_kernel_timing(True)
         for i in range(steps):
@@ -489,6 +512,7 @@ def main():
                                                      f"adapters={l2.layout.n_adapters}",
                                          "ms_per_step": round(ms2, 4), "tflops": round(f2 / (ms2 * 1e-3) / 1e12, 1),
                                          "tokens_per_s": round(l2.layout.T / (ms2 * 1e-3), 1), "input_sets": r2.n_sets,
+                                         "graph_replay_ms_per_step": round(graph_ms(r2.step, r2.n_sets), 4),
                                          "kernels": kernel_table(l2, k2)}))
                 if cfg != 4:
                     del r2
@@ -509,6 +533,7 @@ def main():
                                                "in order then backward in reverse, one stream",
                                    "ms_per_step": round(ms4, 4), "tflops": round(f4 / (ms4 * 1e-3) / 1e12, 1),
                                    "tokens_per_s": round(entries[0][0].layout.T / (ms4 * 1e-3), 1),
+                                   "graph_replay_ms_per_step": round(graph_ms(layer_step, min(r.n_sets for r in runs)), 4),
                                    "linears": [e for _, _, e in entries]})
                 del runs
                 for i in range(len(entries)):
