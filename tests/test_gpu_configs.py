@@ -61,7 +61,7 @@ def test_config2_full_tensors():
     assert scaled_err(ys, y_o[rows]) < 1e-12
 
 
-def check_full_size(lin, n_whole_tiles=16, n_random=256):
+def check_full_size(lin, n_whole_tiles=16, n_random=256, w_layout=0):
     import torch
     import gpu_harness as gh
     from paper_2508_02932_amd import plora
@@ -69,9 +69,10 @@ def check_full_size(lin, n_whole_tiles=16, n_random=256):
     lay = lin.layout
     t0 = time.time()
     t = lin.tensors()
-    say(f"[case] {lin.name} T={lay.T} D={lin.D} K={lin.K} ranks={lay.rank.tolist()} (inputs drawn in {time.time() - t0:.1f} s)")
+    say(f"[case] {lin.name} T={lay.T} D={lin.D} K={lin.K} ranks={lay.rank.tolist()} w_layout={w_layout} "
+        f"(inputs drawn in {time.time() - t0:.1f} s)")
     p = make_problem(oracle, lin, t)
-    dp = gh.upload(lin, t)
+    dp = gh.upload(lin, t, w_layout)
     say("  forward")
     gh.forward(dp)
     torch.cuda.synchronize()
@@ -135,6 +136,12 @@ def test_config4_full_size(which):
 @pytest.mark.parametrize("which", [0, 1], ids=["attn", "mlp_up"])
 def test_config5_full_size(which):
     check_full_size(wl.config(5)[which])
+
+
+def test_config5_mlp_up_full_size_weight_stored_out_in():
+    """The largest linear with W stored [d_out][d_in]: the two GEMM forms in the other direction each, at full size."""
+    from paper_2508_02932_amd import plora
+    check_full_size(wl.config(5)[1], w_layout=plora.PLORA_W_OUT_IN)
 
 
 def test_odd_shapes_many_tiles():
