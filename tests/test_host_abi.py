@@ -35,9 +35,9 @@ def test_library_exports_every_declared_symbol():
 
 
 def mk(T=8, D=16, K=24, seg_off=(0, 3, 8), seg_adapter=(0, 1), rank=(4, 8), scale=(1.0, 2.0),
-       dtype=plora.PLORA_BF16):
+       dtype=plora.PLORA_BF16, w_layout=0):
     return plora.Desc(T, D, K, np.array(seg_off), np.array(seg_adapter), np.array(rank),
-                      np.array(scale), dtype)
+                      np.array(scale), dtype, w_layout)
 
 
 def test_validate_codes():
@@ -90,6 +90,44 @@ def test_entry_points_reject_before_touching_the_device():
     assert bwd(0x1004, 0x1000, tabp, tabp) == 6
     nulltab = (C.c_void_p * 2)(0x1000, None)
     assert bwd(0x1000, 0x1000, C.cast(nulltab, C.c_void_p), tabp) == 1
+
+
+def test_later_entry_points_reject_before_touching_the_device():
+    """The stand-alone low-rank calls, the NF4 calls and the weight layout flag: same rules, same codes."""
+    L = plora.lib()
+    d = mk()
+    tab = (C.c_void_p * 2)(0x1000, 0x2000)
+    tabp = C.cast(tab, C.c_void_p)
+    # weight layout: only the two named values
+    assert plora.plora_validate(mk(w_layout=plora.PLORA_W_OUT_IN)) == 0
+    assert plora.plora_validate(mk(w_layout=2)) == 8
+    assert plora.plora_workspace_bytes(mk(w_layout=2)) == 0
+    # stand-alone low-rank calls: their own workspace size, at least the fused calls' for d_out >= d_in
+    lw = plora.plora_lora_workspace_bytes(d)
+    assert lw >= plora.plora_workspace_bytes(d) > 0
+    lf = lambda x, A, B, y, ws, n: L.plora_lora_fwd(d.ref, x, A, B, y, None, ws, n, None)
+    assert lf(None, tabp, tabp, 0x1000, 0x1000, lw) == 1
+    assert lf(0x1000, tabp, None, 0x1000, 0x1000, lw) == 1
+    assert lf(0x1000, tabp, tabp, None, 0x1000, lw) == 1
+    assert lf(0x1000, tabp, tabp, 0x1004, 0x1000, lw) == 6
+    assert lf(0x1000, tabp, tabp, 0x1000, 0x1000, lw - 1) == 7
+    lb = lambda dy, dx, dA, dB: L.plora_lora_bwd(d.ref, 0x1000, tabp, tabp, dy, None, dx, dA, dB, 0x1000, lw, None)
+    assert lb(None, 0x1000, tabp, tabp) == 1
+    assert lb(0x1000, 0x1000, None, tabp) == 1
+    assert lb(0x1000, 0x1002, tabp, tabp) == 6
+    # NF4: the workspace adds the expanded weight behind the ordinary one; blocks of 64 weights
+    nw = plora.plora_nf4_workspace_bytes(d)
+    assert nw >= plora.plora_workspace_bytes(d) + d.d_in * d.d_out * 2
+    assert plora.plora_nf4_workspace_bytes(mk(D=3, K=5, dtype=plora.PLORA_F32)) == 0
+    nf = lambda codes, absmax, y, ws, n: L.plora_linear_fwd_nf4(d.ref, 0x1000, codes, absmax, tabp, tabp, y, None, ws, n, None)
+    assert nf(None, 0x1000, 0x1000, 0x1000, nw) == 1
+    assert nf(0x1000, 0x1004, 0x1000, 0x1000, nw) == 6
+    assert nf(0x1000, 0x1000, 0x1000, 0x1000, plora.plora_workspace_bytes(d)) == 7
+    assert nf(0x1000, 0x1000, None, 0x1000, nw) == 1               # the inner call's checks come before the expansion
+    assert L.plora_nf4_dequantize(0x1000, 0x1000, 100, 0, 0x1000, None) == 2
+    assert L.plora_nf4_dequantize(0x1000, 0x1000, 128, 5, 0x1000, None) == 8
+    assert L.plora_nf4_dequantize(None, 0x1000, 128, 0, 0x1000, None) == 1
+    assert L.plora_nf4_dequantize(0x1000, 0x1000, 0, 0, None, None) == 0
 
 
 def brute_force_metadata(seg_off, seg_adapter, rank, block_rows):
