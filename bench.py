@@ -15,7 +15,11 @@ Prints ONE JSON line:
                         also as a fraction of the ceilings measured in this run (plain streaming read,
                         MFMA-only loop)
   per_config            the other configurations: 2, 3 (both linears), 4 (seven linears of a decoder layer,
-                        forward in order then backward in reverse on one stream, with the total), 5 (attention)
+                        forward in order then backward in reverse on one stream, with the total), 5 (attention),
+                        each also replayed from a HIP graph; then the headline linear with W stored the other
+                        way round and with W kept in both layouts
+  lora_only             plora_lora_fwd / plora_lora_bwd on the headline workload (in-place update kernel)
+  nf4_base              the headline step on a 4-bit NF4 base weight (expansion kernel, slowdown)
   cpu_baseline          the fp64 oracle on a bounded sample of the headline workload, on the host cores
 Inputs of a step rotate over enough distinct sets of x / dy (more than 512 MB of them) that no kernel
 finds its input in the 256 MB last-level cache from the step before.
