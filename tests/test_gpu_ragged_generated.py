@@ -36,19 +36,20 @@ def ragged_linear(draw):
 
 @settings(max_examples=24, deadline=None, derandomize=True, database=None, phases=[Phase.generate],
           report_multiple_bugs=False, suppress_health_check=list(HealthCheck))
-@given(lin=ragged_linear(), save_h=st.booleans())
-def test_generated_ragged_cases(lin, save_h):
+@given(lin=ragged_linear(), save_h=st.booleans(), w_layout=st.sampled_from([0, 0, 1]))
+def test_generated_ragged_cases(lin, save_h, w_layout):
     import torch
     import gpu_harness as gh
     lay = lin.layout
     print(f"[case] {lin.name} T={lay.T} D={lin.D} K={lin.K} ranks={lay.rank.tolist()} "
-          f"segs={np.diff(lay.seg_off).tolist()} adapters={lay.seg_adapter.tolist()} save_h={save_h}", flush=True)
+          f"segs={np.diff(lay.seg_off).tolist()} adapters={lay.seg_adapter.tolist()} save_h={save_h} "
+          f"w_layout={w_layout}", flush=True)
     sys.stdout.flush()
     t = lin.tensors()
     p = make_problem(oracle, lin, t)
     y_o, h_o = oracle.loops.forward(p)
     dx_o, _, dA_o, dB_o = oracle.loops.backward(p, t.dy)
-    dp = gh.upload(lin, t)
+    dp = gh.upload(lin, t, w_layout)
     gh.forward(dp, save_h=save_h)
     gh.backward(dp, use_saved_h=save_h)
     torch.cuda.synchronize()
@@ -58,6 +59,48 @@ def test_generated_ragged_cases(lin, save_h):
     if lay.T:
         errs["y"] = scaled_err(gh.to_np(dp.y), y_o)
         errs["dx"] = scaled_err(gh.to_np(dp.dx), dx_o)
+    if save_h and lay.sum_Lr() > 0:
+        errs["h"] = scaled_err(gh.ragged_h_to_rows(lin, gh.to_np(dp.h)[:lay.sum_Lr()]), h_o)
+    for k in range(lay.n_adapters):
+        errs[f"dA{k}"] = scaled_err(gh.to_np(dp.dA[k]), dA_o[k])
+        errs[f"dB{k}"] = scaled_err(gh.to_np(dp.dB[k]), dB_o[k])
+    for k, v in errs.items():
+        assert np.isfinite(v) and v <= tol, (lin.name, k, v, tol)
+
+
+@settings(max_examples=12, deadline=None, derandomize=True, database=None, phases=[Phase.generate],
+          report_multiple_bugs=False, suppress_health_check=list(HealthCheck))
+@given(lin=ragged_linear(), save_h=st.booleans())
+def test_generated_ragged_cases_stand_alone_low_rank(lin, save_h):
+    """The same generator through plora_lora_fwd / plora_lora_bwd: y and dx hold arbitrary values of the I/O type on
+    entry and must come back as those values plus the oracle's low-rank term (the oracle run with W = 0)."""
+    import torch
+    import gpu_harness as gh
+    lay = lin.layout
+    print(f"[case] lora-only {lin.name} T={lay.T} D={lin.D} K={lin.K} ranks={lay.rank.tolist()} "
+          f"segs={np.diff(lay.seg_off).tolist()} adapters={lay.seg_adapter.tolist()} save_h={save_h}", flush=True)
+    sys.stdout.flush()
+    t = lin.tensors()
+    rng = np.random.default_rng(lay.T + 7)
+    rnd = wl.round_to_bf16 if lin.dtype == "bf16" else (lambda a: a.astype(np.float32))
+    y_in = rnd(rng.standard_normal((lay.T, lin.K)).astype(np.float32))
+    dx_in = rnd(rng.standard_normal((lay.T, lin.D)).astype(np.float32))
+    t.W = np.zeros_like(t.W)
+    p0 = make_problem(oracle, lin, t)
+    y_d, h_o = oracle.loops.forward(p0)
+    dx_d, _, dA_o, dB_o = oracle.loops.backward(p0, t.dy)
+    dp = gh.upload(lin, t, lora_only=True)
+    dp.y.copy_(gh.to_dev(y_in, lin.dtype))
+    dp.dx.copy_(gh.to_dev(dx_in, lin.dtype))
+    gh.lora_forward(dp, save_h=save_h)
+    gh.lora_backward(dp, use_saved_h=save_h)
+    torch.cuda.synchronize()
+    gh.check_guards(dp)
+    tol = TOL[lin.dtype]
+    errs = {}
+    if lay.T:
+        errs["y"] = scaled_err(gh.to_np(dp.y), y_in.astype(np.float64) + y_d)
+        errs["dx"] = scaled_err(gh.to_np(dp.dx), dx_in.astype(np.float64) + dx_d)
     if save_h and lay.sum_Lr() > 0:
         errs["h"] = scaled_err(gh.ragged_h_to_rows(lin, gh.to_np(dp.h)[:lay.sum_Lr()]), h_o)
     for k in range(lay.n_adapters):
