@@ -19,9 +19,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
 
 
-def _compile(src: str) -> str:
-    obj = os.path.join(OBJ, src.replace(".hip", ".o"))
-    cmd = ["hipcc", *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+def _compile(src: str, obj_dir: str = OBJ, extra=()) -> str:
+    obj = os.path.join(obj_dir, src.replace(".hip", ".o"))
+    cmd = ["hipcc", *FLAGS, *extra, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     err = "\n".join(l for l in res.stderr.splitlines() if "packed-fp32-ops" not in l)
     if res.returncode != 0:
@@ -44,6 +44,23 @@ def build(verbose: bool = False) -> str:
         if verbose:
             print("built", lib)
     return LIB
+
+
+def build_variant(lib_path: str, extra_flags, sources=("gemm_bf16.hip",)) -> str:
+    """A copy of libplora.so at lib_path in which `sources` are compiled with extra flags (tuning runs; the other
+    objects are taken from the last regular build)."""
+    obj_dir = lib_path + ".obj"
+    os.makedirs(obj_dir, exist_ok=True)
+    objs = []
+    for src in SOURCES:
+        if src in sources:
+            objs.append(_compile(src, obj_dir, tuple(extra_flags)))
+        else:
+            objs.append(os.path.join(OBJ, src.replace(".hip", ".o")))
+    res = subprocess.run(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib_path, *objs], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("link failed:\n" + res.stderr)
+    return lib_path
 
 
 if __name__ == "__main__":

@@ -40,6 +40,14 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BM = 256, BN = 256;
 
+// no-ops behind the alignment point in front of the kernel's loops, per form (see the kernel)
+#ifndef PLORA_GEMM_PAD_FWD
+#define PLORA_GEMM_PAD_FWD 1
+#endif
+#ifndef PLORA_GEMM_PAD_DX
+#define PLORA_GEMM_PAD_DX 4
+#endif
+
 // two floats -> packed bf16 pair, round to nearest even (one v_cvt_pk_bf16_f32 on gfx950)
 __device__ inline uint32_t pack_bf16x2(float lo, float hi)
 {
@@ -428,10 +436,10 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
     // second) and through a second-order effect: compute units that share an instruction cache fall a few cycles out
     // of step with one another, and that decides whether the workgroups that stream the same rows of S and columns
     // of W ask the L2 for a line one after the other (one miss, the rest hits) or at the same instant (every one a
-    // miss: 1.9e8 against 5.9e8 L2 misses per launch).  The offsets were chosen by measurement, one per form;
-    // any change to the code from here to the end of the kernel calls for a new sweep.
-    if (FWD) asm volatile(".p2align 8\n\ts_nop 0" ::: "memory");
-    else asm volatile(".p2align 8\n\ts_nop 0\n\ts_nop 0\n\ts_nop 0\n\ts_nop 0" ::: "memory");
+    // miss: 1.9e8 against 5.9e8 L2 misses per launch).  The offsets (PLORA_GEMM_PAD_FWD / _DX no-ops, one value per
+    // form) were chosen by measurement; any change to the code from here to the end of the kernel calls for a new sweep
+    // (python -m paper_2508_02932_amd.sweep_placement builds and times the eight candidates).
+    asm volatile(".p2align 8\n\t.rept %0\n\ts_nop 0\n\t.endr" ::"n"(FWD ? PLORA_GEMM_PAD_FWD : PLORA_GEMM_PAD_DX) : "memory");
     int vb = blockIdx.x;
     set_tile(vb);
     prologue();

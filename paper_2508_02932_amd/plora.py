@@ -15,7 +15,8 @@ from typing import List, Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libplora.so")
+# PLORA_LIBRARY: another build of the same library (tuning runs of sweep_placement.py); normally unset
+LIB_PATH = os.environ.get("PLORA_LIBRARY") or os.path.join(_HERE, "libplora.so")
 
 PLORA_BF16, PLORA_F32 = 0, 1
 PLORA_W_IN_OUT, PLORA_W_OUT_IN = 0, 1
