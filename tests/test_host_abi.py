@@ -175,3 +175,37 @@ def test_metadata_int64_offsets():
     d = plora.Desc(2 ** 25, 64, 64, seg_off, np.array([0, 1]), np.array([128, 128]), np.ones(2), plora.PLORA_BF16)
     h_off, _ = plora.plora_build_metadata(d, 1 << 20)
     assert h_off.tolist() == [0, 2 ** 31, 2 ** 32]
+
+
+def test_host_calls_from_many_threads_agree():
+    """The metadata cache sits behind a lock: eight threads asking for the derived tables of 40 different descriptions
+    (more than the cache holds, so entries are evicted and rebuilt all the time) get, every time, the answer a
+    single thread gets."""
+    import threading
+    rng = np.random.default_rng(77)
+    descs = []
+    for i in range(40):
+        n_seg, n_ad = int(rng.integers(1, 9)), int(rng.integers(1, 6))
+        lens = rng.integers(0, 500, size=n_seg)
+        seg_off = np.concatenate([[0], np.cumsum(lens)])
+        descs.append(plora.Desc(int(seg_off[-1]), 8 * int(rng.integers(1, 30)), 8 * int(rng.integers(1, 30)), seg_off,
+                                rng.integers(-1, n_ad, size=n_seg), rng.integers(1, 129, size=n_ad),
+                                np.ones(n_ad), plora.PLORA_BF16, int(rng.integers(0, 2))))
+    want = [(plora.plora_workspace_bytes(d), plora.plora_h_elems(d), plora.plora_debug_metadata(d)[2].tobytes()) for d in descs]
+    errors = []
+
+    def worker(seed):
+        order = np.random.default_rng(seed).permutation(len(descs))
+        for _ in range(3):
+            for i in order:
+                got = (plora.plora_workspace_bytes(descs[i]), plora.plora_h_elems(descs[i]),
+                       plora.plora_debug_metadata(descs[i])[2].tobytes())
+                if got != want[i]:
+                    errors.append(i)
+
+    threads = [threading.Thread(target=worker, args=(s,)) for s in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors
