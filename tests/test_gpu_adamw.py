@@ -95,6 +95,15 @@ def test_adamw_more_tensors_than_one_launch_carries():
     run_steps("bf16", 72, 56, [1 + (7 * k) % 24 for k in range(n)], hps, 2)
 
 
+def test_adamw_at_the_size_of_configuration_5():
+    """All 64 adapter matrices of the largest linear (8192 -> 28672, 32 adapters, 41.6 M parameters): the launch
+    configuration bench.py times, every element against the oracle."""
+    lay = wl.config(5)[1].layout
+    ranks = [int(r) for r in lay.rank]
+    hps = [Hyper(1e-4 * (1 + k % 5), 0.9, 0.999 if k % 2 else 0.95, 1e-8, 0.01 * (k % 3), 1 + k % 7) for k in range(len(ranks))]
+    run_steps("bf16", 8192, 28672, ranks, hps, 1, seed=5)
+
+
 def test_adamw_rejects_bad_arguments():
     import torch
     import gpu_harness as gh

@@ -143,3 +143,53 @@ def test_lora_only_errors():
     with pytest.raises(plora.PloraError) as e:
         plora.plora_lora_fwd(dp.desc, dp.x, dp.A, dp.B, None, None, dp.ws)
     assert e.value.code == 1                                      # PLORA_ERR_NULL
+
+
+def test_lora_only_config5_mlp_up_full_size():
+    """The largest linear through the stand-alone calls, in the launch configuration bench.py times: h, dA_k, dB_k of
+    every adapter in full; y and dx on two whole 256-row tiles, the rows around every segment boundary and random rows
+    against the oracle (run with W = 0 on those rows, added to what the buffers held); every other row must differ
+    from its input by a finite amount, and rows without an adapter not at all (there are none here, but the base
+    values of all rows are kept for the comparison)."""
+    import time
+    import torch
+    import gpu_harness as gh
+    import fullsize_checks as fc
+    lin = wl.config(5)[1]
+    lay = lin.layout
+    t = lin.tensors()
+    say(f"[case] lora-only {lin.name} T={lay.T} D={lin.D} K={lin.K}")
+    dp = gh.upload(lin, t, lora_only=True)
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    y_in = torch.randn(dp.y.shape, device="cuda", generator=gen).to(torch.bfloat16)
+    dx_in = torch.randn(dp.dx.shape, device="cuda", generator=gen).to(torch.bfloat16)
+    dp.y.copy_(y_in)
+    dp.dx.copy_(dx_in)
+    gh.lora_forward(dp)
+    gh.lora_backward(dp)
+    torch.cuda.synchronize()
+    gh.check_guards(dp)
+    p = make_problem(oracle, lin, t)
+    errs = {"h": fc.compare(gh.ragged_h_to_rows(lin, gh.to_np(dp.h)), oracle.matmul.low_rank_activation(p))}
+    dA_o, dB_o = oracle.matmul.low_rank_gradients(p, t.dy)
+    for k in range(lay.n_adapters):
+        errs[f"dA{k}"] = fc.compare(gh.to_np(dp.dA[k]), dA_o[k])
+        errs[f"dB{k}"] = fc.compare(gh.to_np(dp.dB[k]), dB_o[k])
+    rows = fc.plan_rows(lay.seg_off, 2, 64, np.random.default_rng(3))
+    t0 = time.time()
+    t.W = np.zeros_like(t.W)
+    sub = make_problem(oracle, lin, t).take_rows(rows)
+    y_d, _ = oracle.matmul.forward(sub)
+    dx_d, _, _, _ = oracle.matmul.backward(sub, t.dy[rows])
+    say(f"  oracle: low-rank terms of {len(rows)} rows in {time.time() - t0:.1f} s")
+    idx = torch.from_numpy(rows).cuda()
+    errs["y"] = fc.compare(gh.to_np(dp.y[idx]), gh.to_np(y_in[idx]).astype(np.float64) + y_d)
+    errs["dx"] = fc.compare(gh.to_np(dp.dx[idx]), gh.to_np(dx_in[idx]).astype(np.float64) + dx_d)
+    say("  errors " + " ".join(f"{k}={v:.2e}" for k, v in errs.items() if k in ("h", "y", "dx")) + f" max {max(errs.values()):.2e}")
+    assert all(np.isfinite(v) and v <= TOL["bf16"] for v in errs.values()), errs
+    # every row was updated by something finite and of the size of a low-rank term, none was skipped or overwritten
+    dy_rows = (dp.y.float() - y_in.float()).abs().amax(dim=1)
+    ddx_rows = (dp.dx.float() - dx_in.float()).abs().amax(dim=1)
+    assert bool(torch.isfinite(dy_rows).all()) and bool(torch.isfinite(ddx_rows).all())
+    assert float(dy_rows.min()) > 0 and float(ddx_rows.min()) > 0
+    assert float(dy_rows.max()) < 64 and float(ddx_rows.max()) < 64
