@@ -36,6 +36,11 @@ def test_dequantize_bit_exact(n, dtype):
     assert bool((out[n:] == 7.0).all())
 
 
+def test_dequantize_bit_exact_at_the_size_of_the_largest_weight():
+    """8192 x 28672 weights (configuration 5, mlp_up), the launch bench.py times."""
+    test_dequantize_bit_exact(8192 * 28672, "bf16")
+
+
 def run_nf4_layer(lin, w_layout=0, impl=None):
     import torch
     import gpu_harness as gh
