@@ -52,6 +52,7 @@ extern "C" {
 #define PLORA_MAX_RANK      128   /* the paper's rank range ends at 128 (Table 1)              */
 #define PLORA_MAX_ADAPTERS  256
 #define PLORA_MAX_SEGMENTS 1024
+#define PLORA_MAX_GROUP       4   /* projections per grouped call (q / k / v; gate / up)          */
 
 typedef enum {
     PLORA_OK = 0,
@@ -66,7 +67,9 @@ typedef enum {
     PLORA_ERR_WORKSPACE = 7,    /* workspace NULL or smaller than plora_workspace_bytes()       */
     PLORA_ERR_UNSUPPORTED = 8,  /* unknown dtype or weight layout                               */
     PLORA_ERR_HIP = 9,          /* a HIP call failed (launch error)                             */
-    PLORA_ERR_INTERNAL = 10     /* host memory allocation failed or another internal error      */
+    PLORA_ERR_INTERNAL = 10,    /* host memory allocation failed or another internal error      */
+    PLORA_ERR_GROUP = 11        /* grouped call: n_proj outside [1, PLORA_MAX_GROUP], or the
+                                   projections differ in dtype, T, d_in, segments or adapters    */
 } plora_status;
 
 typedef enum { PLORA_BF16 = 0, PLORA_F32 = 1 } plora_dtype;
@@ -188,6 +191,37 @@ plora_status plora_lora_fwd(const plora_desc *desc, const void *x, const void *c
 plora_status plora_lora_bwd(const plora_desc *desc, const void *x, const void *const *A, const void *const *B,
                             const void *dy, const float *h_saved, void *dx, float *const *dA, float *const *dB,
                             void *workspace, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Several projections on one x (q / k / v of an attention block, gate / up of an MLP): appendix C.2's concatenation of
+ * the adapters into one tensor, applied across the projections that share an input.  Projection p is an ordinary
+ * layer of its own - its W_p, d_out, ranks r_{k,p}, scales, A_{k,p}, B_{k,p}, weight layout - and every result is what
+ * plora_linear_fwd / _bwd give for it alone.  What is shared is the traffic: x_t A_{k,p} for all p comes from one pass
+ * over x against the A_{k,p} laid side by side, and dA_{k,p} for all p from one pass over x against the g_{t,p} laid
+ * side by side.  Projections are fused as long as their ranks, each rounded up to a multiple of 16, sum to at most
+ * PLORA_MAX_RANK for every adapter; a group beyond that is cut into several fused passes, in the order given.
+ *   group->desc   HOST array of n_proj descriptions with the same dtype, T, d_in, n_seg, seg_off, seg_adapter and
+ *                 n_adapters (PLORA_ERR_GROUP otherwise)
+ *   W, y, dy, dx, h_saved   HOST arrays of n_proj DEVICE pointers, entry p as in the plain call for projection p
+ *                 (dx, h_saved: the array or single entries may be NULL; dx[p] is projection p's own dy_p W_p^T +
+ *                 g_p A_p^T - summing them over p is the caller's)
+ *   A, B, dA, dB  HOST arrays of n_proj HOST arrays of n_adapters DEVICE pointers; dA / dB: the array, or entry p of
+ *                 both, may be NULL (no weight gradients for that projection)
+ * The workspace must hold plora_group_workspace_bytes(group) bytes (0 for an invalid group).  PLORA_F32 groups are
+ * accepted and run projection by projection.
+ */
+typedef struct {
+    int32_t n_proj;               /* 1 .. PLORA_MAX_GROUP                                          */
+    const plora_desc *desc;       /* HOST [n_proj]                                                  */
+} plora_group;
+size_t plora_group_workspace_bytes(const plora_group *group);
+plora_status plora_group_fwd(const plora_group *group, const void *x, const void *const *W,
+                             const void *const *const *A, const void *const *const *B, void *const *y,
+                             float *const *h_saved, void *workspace, size_t ws_bytes, void *hip_stream);
+plora_status plora_group_bwd(const plora_group *group, const void *x, const void *const *W,
+                             const void *const *const *A, const void *const *const *B, const void *const *dy,
+                             const float *const *h_saved, void *const *dx, float *const *const *dA,
+                             float *const *const *dB, void *workspace, size_t ws_bytes, void *hip_stream);
 
 /*
  * The layer on a base weight stored as 4-bit NormalFloat (NF4, the storage QLoRA publishes; the paper applies packed

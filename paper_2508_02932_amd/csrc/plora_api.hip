@@ -276,9 +276,16 @@ static MetaView device_view(const HostMeta &m, const WorkspaceLayout &L, char *w
     return view_of(tables_at(ws + L.meta, m.layout));
 }
 
+// Steps of a call, so that a grouped call can run a fused pass of its own between them (a plain call runs them all).
+enum : unsigned {
+    kStepPrep = 1u, kStepShrink = 2u, kStepMain = 4u,      // forward: prep, shrink, GEMM (or stand-alone update)
+    kStepDh = 8u, kStepDb = 16u, kStepDa = 32u, kStepDx = 64u,   // backward: prep, shrink, dH, dB, dA, dX
+    kStepsAll = 127u
+};
+
 static plora_status forward_impl(const plora_desc *desc, const void *x, const void *W, const void *const *A,
                                  const void *const *B, void *y, float *h_saved, void *workspace, size_t ws_bytes,
-                                 void *hip_stream, bool lora_only = false, bool check_only = false)
+                                 void *hip_stream, bool lora_only = false, bool check_only = false, unsigned steps = kStepsAll)
 {
     Call c;
     plora_status ps = prepare(desc, x, W, A, B, nullptr, nullptr, workspace, ws_bytes, lora_only, c);
@@ -295,14 +302,17 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
     const bool lora = m.hdr.n_blocks > 0;
     const bool bf = desc->dtype == PLORA_BF16;
     const bool w_out_in = m.hdr.w_out_in != 0;
-    { Bracket b(6, st);
-      PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + L.meta, reinterpret_cast<uint32_t *>(ws + L.desc), ws + L.zero,
-                         ws + L.at, ws + L.ap, bf && lora, false, bf && lora && (w_out_in || lora_only), nullptr, nullptr, st)); }
+    if (steps & kStepPrep) {
+        Bracket b(6, st);
+        PL_TRY(launch_prep(c.words, m.n_words, m.hdr, ws + L.meta, reinterpret_cast<uint32_t *>(ws + L.desc), ws + L.zero,
+                           ws + L.at, ws + L.ap, bf && lora, false, bf && lora && (w_out_in || lora_only), nullptr, nullptr, st));
+    }
     float *hf = h_saved ? h_saved : reinterpret_cast<float *>(ws + L.hf);
 
     if (desc->dtype == PLORA_F32) {
         const float *xf = static_cast<const float *>(x);
-        if (lora) { Bracket b(2, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hf, st)); }
+        if (lora && (steps & kStepShrink)) { Bracket b(2, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hf, st)); }
+        if (!(steps & kStepMain)) return PLORA_OK;
         if (lora_only) {
             Bracket b(8, st);
             PL_TRY(launch_f32_expand(mv, m.hdr, true, static_cast<float *>(y), hf, st));
@@ -315,10 +325,11 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
 
     void *at = ws + L.at, *hb = ws + L.hb;
     float *part = reinterpret_cast<float *>(ws + L.part);
-    if (lora) {
+    if (lora && (steps & kStepShrink)) {
         Bracket b(2, st);
         PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + L.zero, part, h_saved, hb, nullptr, false, st));
     }
+    if (!(steps & kStepMain)) return PLORA_OK;
     if (lora_only) {
         // the padded buffer holds B_k^T [d_out][rp]; the tables carry its offsets for d_in rows unless W's layout says d_out
         Bracket b(8, st);
@@ -333,7 +344,7 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
 static plora_status backward_impl(const plora_desc *desc, const void *x, const void *W, const void *const *A,
                                   const void *const *B, const void *dy, const float *h_saved, void *dx, float *const *dA,
                                   float *const *dB, void *workspace, size_t ws_bytes, void *hip_stream, bool lora_only = false,
-                                  bool check_only = false)
+                                  bool check_only = false, unsigned steps = kStepsAll)
 {
     const bool want_w = (dA != nullptr) || (dB != nullptr);
     if (desc && want_w && desc->n_adapters > 0 && (!dA || !dB)) {
@@ -360,7 +371,7 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
     if ((desc->T == 0 && !any_w) || check_only) return PLORA_OK;
 
     const MetaView mv = device_view(m, L, ws);
-    {
+    if (steps & kStepPrep) {
         const bool bf = desc->dtype == PLORA_BF16;
         const bool need_shrink = any_w && !h_saved;
         const bool tr = bf && lora && any_w && h_saved;
@@ -378,16 +389,16 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
         float *gf = reinterpret_cast<float *>(ws + L.gf);
         const float *hf = h_saved;
         if (lora && any_w && !hf) {
-            Bracket b(2, st);
             float *hw = reinterpret_cast<float *>(ws + L.hf);
-            PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hw, st));
+            if (steps & kStepShrink) { Bracket b(2, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 0, xf, desc->d_in, hw, st)); }
             hf = hw;
         }
-        if (lora) { Bracket b(3, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 1, dyf, desc->d_out, gf, st)); }
+        if (lora && (steps & kStepDh)) { Bracket b(3, st); PL_TRY(launch_f32_lowrank(mv, m.hdr, 1, dyf, desc->d_out, gf, st)); }
         if (any_w) {
-            { Bracket b(4, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, false, dyf, desc->d_out, hf, st)); }
-            { Bracket b(5, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, true, xf, desc->d_in, gf, st)); }
+            if (steps & kStepDb) { Bracket b(4, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, false, dyf, desc->d_out, hf, st)); }
+            if (steps & kStepDa) { Bracket b(5, st); PL_TRY(launch_f32_wgrad(mv, m.hdr, true, xf, desc->d_in, gf, st)); }
         }
+        if (!(steps & kStepDx)) return PLORA_OK;
         if (dx && desc->T > 0 && lora_only) {
             Bracket b(8, st);
             PL_TRY(launch_f32_expand(mv, m.hdr, false, static_cast<float *>(dx), gf, st));
@@ -403,17 +414,20 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
     float *part = reinterpret_cast<float *>(ws + L.part);
     float *wpart = reinterpret_cast<float *>(ws + L.wpart);
     if (lora) {
-        if (any_w && !h_saved) {
+        if (any_w && !h_saved && (steps & kStepShrink)) {
             Bracket b(2, st);
             PL_TRY(launch_skinny_bf16(mv, m.hdr, 0, x, desc->d_in, at, ws + L.zero, part, nullptr, nullptr, zt_h, false, st));
         }
-        { Bracket b(3, st);
-          PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, ws + L.zero, part, nullptr, gb, any_w ? zt_g : nullptr, true, st)); }
+        if (steps & kStepDh) {
+            Bracket b(3, st);
+            PL_TRY(launch_skinny_bf16(mv, m.hdr, 1, dy, desc->d_out, nullptr, ws + L.zero, part, nullptr, gb, any_w ? zt_g : nullptr, true, st));
+        }
     }
     if (any_w) {
-        { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + L.zero, wpart, m.split_dB, m.r16_total, m.n_active, st)); }
-        { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + L.zero, wpart, m.split_dA, m.r16_total, m.n_active, st)); }
+        if (steps & kStepDb) { Bracket b(4, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, false, dy, desc->d_out, zt_h, ws + L.zero, wpart, m.split_dB, m.r16_total, m.n_active, st)); }
+        if (steps & kStepDa) { Bracket b(5, st); PL_TRY(launch_tokcontract_bf16(mv, m.hdr, true, x, desc->d_in, zt_g, ws + L.zero, wpart, m.split_dA, m.r16_total, m.n_active, st)); }
     }
+    if (!(steps & kStepDx)) return PLORA_OK;
     if (dx && desc->T > 0 && lora_only) {
         // padded A_k [d_in][rp]; the tables carry its offsets for d_in rows unless W's layout says d_out
         Bracket b(8, st);
@@ -421,6 +435,213 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
     } else if (dx && desc->T > 0) {
         Bracket b(1, st);
         PL_TRY(launch_gemm_bf16(mv, m.hdr, m.hdr.w_out_in != 0, desc->d_out, desc->d_in, dy, W, gb, ap, ws + L.zero, dx, st));
+    }
+    return PLORA_OK;
+}
+
+// ---- grouped calls: several projections on one x -------------------------------------------------------
+// Each projection keeps a workspace of its own inside the group's (so every table and side buffer is where the plain
+// call would put it); behind them lies the partial-tile region of the fused passes.  Projections are fused in cells:
+// consecutive projections whose ranks, each padded to 16, sum to at most PLORA_MAX_RANK for every adapter.
+struct GroupPlan {
+    int n = 0;
+    std::shared_ptr<const HostMeta> m[kMaxGroup];
+    size_t ws_off[kMaxGroup] = {};
+    int cell_of[kMaxGroup] = {};      // cell index of each projection
+    int n_cells = 0;
+    size_t part_off = 0, total = 0;
+};
+
+struct CellShape { int max_r16 = 0, r16_total = 0; };
+
+// Fused ranks of the projections in `members` (indices into the plan).
+static CellShape cell_shape(const GroupPlan &gp, const int *members, int n_members)
+{
+    CellShape c;
+    const int n_ad = gp.m[0]->hdr.n_adapters;
+    for (int k = 0; k < n_ad; ++k) {
+        int sum = 0;
+        for (int i = 0; i < n_members; ++i) sum += gp.m[members[i]]->t.ad[k].r16;
+        c.max_r16 = std::max(c.max_r16, sum);
+        c.r16_total += sum;
+    }
+    return c;
+}
+
+static size_t cell_part_bytes(const GroupPlan &gp, const plora_desc *d0, const CellShape &c)
+{
+    MetaHeader hv = gp.m[0]->hdr;
+    hv.max_r16 = c.max_r16;
+    const size_t shrink = (size_t)skinny_splits(hv, d0->d_in) * hv.n_blocks * kSkinnyRows * c.max_r16 * 4;
+    const int sp = tokc_splits(hv, d0->d_in, gp.m[0]->n_active);
+    const size_t da = sp > 1 ? (size_t)sp * c.r16_total * d0->d_in * 4 : 0;
+    return std::max(shrink, da);
+}
+
+static plora_status plan_group(const plora_group *g, GroupPlan &gp)
+{
+    if (!g) return PLORA_ERR_NULL;
+    if (g->n_proj < 1 || g->n_proj > PLORA_MAX_GROUP) return PLORA_ERR_GROUP;
+    if (!g->desc) return PLORA_ERR_NULL;
+    const plora_desc *d0 = &g->desc[0];
+    for (int p = 0; p < g->n_proj; ++p) {
+        const plora_desc *d = &g->desc[p];
+        plora_status st = validate(d);
+        if (st != PLORA_OK) return st;
+        if (d->dtype != d0->dtype || d->T != d0->T || d->d_in != d0->d_in || d->n_seg != d0->n_seg || d->n_adapters != d0->n_adapters)
+            return PLORA_ERR_GROUP;
+        for (int32_t s = 0; s < d->n_seg; ++s)
+            if (d->seg_off[s + 1] != d0->seg_off[s + 1] || d->seg_adapter[s] != d0->seg_adapter[s]) return PLORA_ERR_GROUP;
+    }
+    gp.n = g->n_proj;
+    size_t o = 0;
+    for (int p = 0; p < gp.n; ++p) {
+        gp.m[p] = meta_of(&g->desc[p]);
+        gp.ws_off[p] = o;
+        o = align_up(o + gp.m[p]->ws.total, 256);
+    }
+    // cells (bf16 with adapters only: the fp32 path is not fused)
+    const bool fuse = d0->dtype == PLORA_BF16 && gp.m[0]->hdr.n_blocks > 0;
+    int members[kMaxGroup], nm = 0, cell = 0;
+    size_t part = 0;
+    for (int p = 0; p < gp.n; ++p) {
+        members[nm] = p;
+        if (nm > 0 && (!fuse || cell_shape(gp, members, nm + 1).max_r16 > PLORA_MAX_RANK)) {
+            if (nm > 1) part = std::max(part, cell_part_bytes(gp, d0, cell_shape(gp, members, nm)));
+            ++cell; members[0] = p; nm = 0;
+        }
+        gp.cell_of[p] = cell;
+        ++nm;
+    }
+    if (nm > 1) part = std::max(part, cell_part_bytes(gp, d0, cell_shape(gp, members, nm)));
+    gp.n_cells = cell + 1;
+    gp.part_off = o;
+    gp.total = align_up(o + part, 256) + 256;
+    return PLORA_OK;
+}
+
+// The fused view of the projections `members` of the plan (all of one cell); small: which side buffer the pass gathers.
+static void group_view(const GroupPlan &gp, char *ws, const int *members, int nm, bool small_is_at, GroupView &gv, MetaHeader &hv)
+{
+    const CellShape c = cell_shape(gp, members, nm);
+    gv.n_proj = nm; gv.max_r16 = c.max_r16; gv.r16_total = c.r16_total; gv.reserved = 0;
+    for (int i = 0; i < kMaxGroup; ++i) {
+        const int p = members[i < nm ? i : 0];
+        const HostMeta &m = *gp.m[p];
+        char *w = ws + gp.ws_off[p];
+        gv.mv[i] = device_view(m, m.ws, w);
+        gv.small[i] = reinterpret_cast<const uint16_t *>(w + (small_is_at ? m.ws.at : m.ws.zt_g));
+    }
+    hv = gp.m[members[0]]->hdr;
+    hv.max_r16 = c.max_r16;
+}
+
+static plora_status group_forward(const plora_group *g, const void *x, const void *const *W, const void *const *const *A,
+                                  const void *const *const *B, void *const *y, float *const *h_saved, void *workspace,
+                                  size_t ws_bytes, void *hip_stream)
+{
+    GroupPlan gp;
+    plora_status ps = plan_group(g, gp);
+    if (ps != PLORA_OK) return ps;
+    if (!W || !y || (g->desc[0].n_adapters > 0 && (!A || !B))) return PLORA_ERR_NULL;
+    if (!workspace || ws_bytes < gp.total) return PLORA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
+    char *ws = static_cast<char *>(workspace);
+    auto run = [&](int p, bool check, unsigned steps) {
+        return forward_impl(&g->desc[p], x, W[p], A ? A[p] : nullptr, B ? B[p] : nullptr, y[p], h_saved ? h_saved[p] : nullptr,
+                            ws + gp.ws_off[p], gp.m[p]->ws.total, hip_stream, false, check, steps);
+    };
+    for (int p = 0; p < gp.n; ++p)
+        if ((ps = run(p, true, kStepsAll)) != PLORA_OK) return ps;
+    if (g->desc[0].T == 0) return PLORA_OK;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    bool fused[kMaxGroup] = {};
+    for (int p = 0; p < gp.n; ++p)
+        for (int q = 0; q < gp.n; ++q) fused[p] = fused[p] || (q != p && gp.cell_of[q] == gp.cell_of[p]);
+    for (int p = 0; p < gp.n; ++p)
+        if ((ps = run(p, false, kStepPrep | (fused[p] ? 0u : kStepShrink))) != PLORA_OK) return ps;
+    for (int c = 0; c < gp.n_cells; ++c) {
+        int members[kMaxGroup], nm = 0;
+        for (int p = 0; p < gp.n; ++p)
+            if (gp.cell_of[p] == c && fused[p]) members[nm++] = p;
+        if (nm < 2) continue;
+        GroupView gv; MetaHeader hv;
+        group_view(gp, ws, members, nm, true, gv, hv);
+        float *hf[kMaxGroup] = {}; void *hb[kMaxGroup] = {}; void *zt[kMaxGroup] = {};
+        for (int i = 0; i < nm; ++i) {
+            hf[i] = h_saved ? h_saved[members[i]] : nullptr;
+            hb[i] = ws + gp.ws_off[members[i]] + gp.m[members[i]]->ws.hb;
+        }
+        Bracket b(2, st);
+        PL_TRY(launch_skinny_group(gv, hv, x, g->desc[0].d_in, ws + gp.ws_off[members[0]] + gp.m[members[0]]->ws.zero,
+                                   reinterpret_cast<float *>(ws + gp.part_off), hf, hb, zt, st));
+    }
+    for (int p = 0; p < gp.n; ++p)
+        if ((ps = run(p, false, kStepMain)) != PLORA_OK) return ps;
+    return PLORA_OK;
+}
+
+static plora_status group_backward(const plora_group *g, const void *x, const void *const *W, const void *const *const *A,
+                                   const void *const *const *B, const void *const *dy, const float *const *h_saved,
+                                   void *const *dx, float *const *const *dA, float *const *const *dB, void *workspace,
+                                   size_t ws_bytes, void *hip_stream)
+{
+    GroupPlan gp;
+    plora_status ps = plan_group(g, gp);
+    if (ps != PLORA_OK) return ps;
+    if (!W || !dy || (g->desc[0].n_adapters > 0 && (!A || !B))) return PLORA_ERR_NULL;
+    if (!workspace || ws_bytes < gp.total) return PLORA_ERR_WORKSPACE;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
+    char *ws = static_cast<char *>(workspace);
+    auto run = [&](int p, bool check, unsigned steps) {
+        return backward_impl(&g->desc[p], x, W[p], A ? A[p] : nullptr, B ? B[p] : nullptr, dy[p], h_saved ? h_saved[p] : nullptr,
+                             dx ? dx[p] : nullptr, dA ? dA[p] : nullptr, dB ? dB[p] : nullptr, ws + gp.ws_off[p],
+                             gp.m[p]->ws.total, hip_stream, false, check, steps);
+    };
+    for (int p = 0; p < gp.n; ++p)
+        if ((ps = run(p, true, kStepsAll)) != PLORA_OK) return ps;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const plora_desc *d0 = &g->desc[0];
+    // which projections want weight gradients, and which of those have to recompute x A_k
+    bool want_w[kMaxGroup] = {}, shrink[kMaxGroup] = {}, fuse_s[kMaxGroup] = {}, fuse_a[kMaxGroup] = {};
+    for (int p = 0; p < gp.n; ++p) {
+        want_w[p] = d0->n_adapters > 0 && ((dA && dA[p]) || (dB && dB[p]));
+        shrink[p] = want_w[p] && !(h_saved && h_saved[p]);
+    }
+    for (int p = 0; p < gp.n; ++p)
+        for (int q = 0; q < gp.n; ++q) {
+            if (q == p || gp.cell_of[q] != gp.cell_of[p]) continue;
+            fuse_s[p] = fuse_s[p] || (shrink[p] && shrink[q]);
+            fuse_a[p] = fuse_a[p] || (want_w[p] && want_w[q]);
+        }
+    for (int p = 0; p < gp.n; ++p)
+        if ((ps = run(p, false, kStepPrep | (fuse_s[p] ? 0u : kStepShrink))) != PLORA_OK) return ps;
+    for (int c = 0; c < gp.n_cells; ++c) {
+        int members[kMaxGroup], nm = 0;
+        for (int p = 0; p < gp.n; ++p)
+            if (gp.cell_of[p] == c && fuse_s[p]) members[nm++] = p;
+        if (nm < 2) continue;
+        GroupView gv; MetaHeader hv;
+        group_view(gp, ws, members, nm, true, gv, hv);
+        float *hf[kMaxGroup] = {}; void *hb[kMaxGroup] = {}; void *zt[kMaxGroup] = {};
+        for (int i = 0; i < nm; ++i) zt[i] = ws + gp.ws_off[members[i]] + gp.m[members[i]]->ws.zt_h;
+        Bracket b(2, st);
+        PL_TRY(launch_skinny_group(gv, hv, x, d0->d_in, ws + gp.ws_off[members[0]] + gp.m[members[0]]->ws.zero,
+                                   reinterpret_cast<float *>(ws + gp.part_off), hf, hb, zt, st));
+    }
+    for (int p = 0; p < gp.n; ++p)
+        if ((ps = run(p, false, kStepDh | kStepDb | (fuse_a[p] ? 0u : kStepDa) | kStepDx)) != PLORA_OK) return ps;
+    for (int c = 0; c < gp.n_cells; ++c) {
+        int members[kMaxGroup], nm = 0;
+        for (int p = 0; p < gp.n; ++p)
+            if (gp.cell_of[p] == c && fuse_a[p]) members[nm++] = p;
+        if (nm < 2) continue;
+        GroupView gv; MetaHeader hv;
+        group_view(gp, ws, members, nm, false, gv, hv);
+        Bracket b(5, st);
+        PL_TRY(launch_tokc_group_dA(gv, hv, x, d0->d_in, ws + gp.ws_off[members[0]] + gp.m[members[0]]->ws.zero,
+                                    reinterpret_cast<float *>(ws + gp.part_off), tokc_splits(hv, d0->d_in, gp.m[0]->n_active),
+                                    gp.m[0]->n_active, st));
     }
     return PLORA_OK;
 }
@@ -471,6 +692,7 @@ const char *plora_status_string(plora_status st)
     case PLORA_ERR_UNSUPPORTED: return "unsupported dtype";
     case PLORA_ERR_HIP: return "HIP launch failed";
     case PLORA_ERR_INTERNAL: return "host memory allocation failed or internal error";
+    case PLORA_ERR_GROUP: return "grouped call: bad number of projections, or they differ in dtype, T, d_in, segments or adapters";
     }
     return "unknown status";
 }
@@ -759,6 +981,34 @@ plora_status plora_lora_bwd(const plora_desc *desc, const void *x, const void *c
 {
     PL_GUARDED(PLORA_ERR_INTERNAL,
         return backward_impl(desc, x, nullptr, A, B, dy, h_saved, dx, dA, dB, workspace, ws_bytes, hip_stream, true);
+    )
+}
+
+size_t plora_group_workspace_bytes(const plora_group *group)
+{
+    PL_GUARDED(0,
+        GroupPlan gp;
+        if (plan_group(group, gp) != PLORA_OK) return 0;
+        return gp.total;
+    )
+}
+
+plora_status plora_group_fwd(const plora_group *group, const void *x, const void *const *W, const void *const *const *A,
+                             const void *const *const *B, void *const *y, float *const *h_saved, void *workspace,
+                             size_t ws_bytes, void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        return group_forward(group, x, W, A, B, y, h_saved, workspace, ws_bytes, hip_stream);
+    )
+}
+
+plora_status plora_group_bwd(const plora_group *group, const void *x, const void *const *W, const void *const *const *A,
+                             const void *const *const *B, const void *const *dy, const float *const *h_saved,
+                             void *const *dx, float *const *const *dA, float *const *const *dB, void *workspace,
+                             size_t ws_bytes, void *hip_stream)
+{
+    PL_GUARDED(PLORA_ERR_INTERNAL,
+        return group_backward(group, x, W, A, B, dy, h_saved, dx, dA, dB, workspace, ws_bytes, hip_stream);
     )
 }
 

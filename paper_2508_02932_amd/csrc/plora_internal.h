@@ -109,6 +109,22 @@ struct MetaView {
     const int32_t *tile_order;  // the GEMM row tiles ordered by extension steps, most first (ties: lower tile first)
 };
 
+// Several projections that read the same x (q / k / v, gate / up), fused along the rank: for adapter k the fused pass
+// treats the rows of the projections' small factors, each padded to 16, as one factor of sum_p r16_{k,p} <= PLORA_MAX_RANK
+// rows (appendix C.2's concatenation of adapters, applied across projections).  The rows stay where each projection's
+// own kernels keep them; the fused kernels gather them 8 rows at a time.  The projections share the segments, so the
+// token blocks, the per-adapter segment lists and the order by token count are those of projection 0.
+constexpr int kMaxGroup = PLORA_MAX_GROUP;
+struct GroupView {
+    int32_t n_proj;               // projections fused in this launch (>= 2)
+    int32_t max_r16;              // largest fused rank among the adapters with tokens
+    int32_t r16_total;            // sum of the fused ranks over all adapters (rows of the dA partial tiles)
+    int32_t reserved;
+    MetaView mv[kMaxGroup];       // each projection's own tables
+    const uint16_t *small[kMaxGroup];   // shrink: its packed-A^T buffer;  dA: its transposed bf16 g
+};
+struct NoGroup { int32_t unused; };
+
 // ---- compact description -----------------------------------------------------------------------
 // 32-bit words: [0,1] T  [2,3] D  [4,5] K  [6] n_seg  [7] n_adapters  [8] n_blocks (computed by the host, fixes the
 // table layout)  [9] bit 0: W is stored [d_out][d_in], bit 1: the sorted order of the GEMM row tiles is the identity (the
@@ -475,6 +491,13 @@ hipError_t launch_expand_bf16(const MetaView &mv, const MetaHeader &h, void *C, 
 hipError_t launch_tokcontract_bf16(const MetaView &mv, const MetaHeader &h, bool want_dA, const void *S,
                                    int64_t C, const void *zt, const void *zero, float *part, int n_split,
                                    int r16_total, int n_active_adapters, hipStream_t st);
+// The same two passes for several projections at once (see GroupView).  hv: projection 0's header with max_r16 replaced
+// by the fused one.  Shrink: hf / hb / zt per projection as in launch_skinny_bf16 (mode 0).  dA: the results go to each
+// projection's own dA_k; n_split must be tokc_splits(hv, C, n_active_adapters).
+hipError_t launch_skinny_group(const GroupView &gv, const MetaHeader &hv, const void *x, int64_t C, const void *zero, float *part,
+                               float *const *hf, void *const *hb, void *const *zt, hipStream_t st);
+hipError_t launch_tokc_group_dA(const GroupView &gv, const MetaHeader &hv, const void *x, int64_t C, const void *zero,
+                                float *part, int n_split, int n_active_adapters, hipStream_t st);
 int tokc_splits(const MetaHeader &h, int64_t C, int n_active_adapters);
 int tokc_tile_columns(const MetaHeader &h, int64_t C, int n_active_adapters);
 int skinny_splits(const MetaHeader &h, int64_t C);

@@ -12,6 +12,7 @@
 // dimensions, not the rank).  Partial tiles of the splits are summed in a fixed order by a small
 // finishing kernel that also writes the bf16 copies the later kernels consume.
 #include "plora_internal.h"
+#include <type_traits>
 
 namespace plora {
 
@@ -54,9 +55,13 @@ __device__ inline void wait_vmcnt_dyn(int n)
 // conflict free).  Wave w owns tokens 32w..32w+31 and every rank block, so nothing is reduced
 // across waves.  Output: the fp32 partial tile [128][r16] of this slice.
 //   mode 0: small matrix = packed A_k^T [r16][C] (rows >= r are zero),  mode 1: B_k [r][C].
+// GROUP (mode 0 only): the small matrix of adapter k is the packed A_k^T of several projections, one below the other
+// (GroupView); mv is projection 0's view, `at` is not used.
+template <bool GROUP>
 __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, const uint16_t *__restrict__ S, int C,
                                                const uint16_t *__restrict__ at, const uint16_t *__restrict__ zero,
-                                               float *__restrict__ part, int stages_per_split)
+                                               float *__restrict__ part, int stages_per_split,
+                                               std::conditional_t<GROUP, GroupView, NoGroup> gv)
 {
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     const int blk = blockIdx.x;
@@ -64,8 +69,25 @@ __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, co
     const AdapterInfo a = mv.ad[g.adapter];
     const int t0 = (blk - g.blk0) * kSkinnyRows;
     const int nt = (g.row1 - g.row0 - t0 < kSkinnyRows) ? g.row1 - g.row0 - t0 : kSkinnyRows;
-    const int nb = g.r16 / 16;
-    const int max_r16 = mv.hdr->max_r16;
+    int r16 = g.r16, max_r16;
+    int p_r16[kMaxGroup];                              // GROUP: rows of each projection's block of the small matrix
+    int64_t p_at[kMaxGroup];                           // ... and where the block starts in that projection's buffer
+    if constexpr (GROUP) {
+        r16 = 0;
+#pragma unroll
+        for (int p = 0; p < kMaxGroup; ++p) {
+            p_r16[p] = 0; p_at[p] = 0;
+            if (p < gv.n_proj) {
+                const AdapterInfo ap = gv.mv[p].ad[g.adapter];
+                p_r16[p] = ap.r16; p_at[p] = ap.at_off;
+                r16 += ap.r16;
+            }
+        }
+        max_r16 = gv.max_r16;
+    } else {
+        max_r16 = mv.hdr->max_r16;
+    }
+    const int nb = r16 / 16;
     const int stage_bytes = SK_XT + max_r16 * SK_BK * 2;
 
     const int lane = threadIdx.x & 63;
@@ -78,8 +100,8 @@ __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, co
     n_st = n_st < stages_per_split ? n_st : stages_per_split;
     if (n_st < 0) n_st = 0;
 
-    const uint16_t *Bm = (mode == 0) ? at + a.at_off : static_cast<const uint16_t *>(a.B);
-    const int brows = (mode == 0) ? g.r16 : g.r;     // rows of the small matrix that exist
+    const uint16_t *Bm = GROUP ? nullptr : (mode == 0) ? at + a.at_off : static_cast<const uint16_t *>(a.B);
+    const int brows = (mode == 0) ? r16 : g.r;       // rows of the small matrix that exist
 
     // ---- loader: every load instruction moves 8 rows x 128 bytes; lane -> (row 8q + lane/8, slot
     // lane%8); slot c' of row u holds chunk c' ^ ((u >> 1) & 7).  Token tile: 16 instructions, wave w
@@ -95,7 +117,7 @@ __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, co
         xok[jj] = u < nt;
         xp[jj] = S + (int64_t)(g.row0 + t0 + (xok[jj] ? u : 0)) * C + (int64_t)st0 * SK_BK + xchunk[jj] * 8;
     }
-    const int nbi = g.r16 / 8;                                    // small-matrix load instructions per stage
+    const int nbi = r16 / 8;                                      // small-matrix load instructions per stage
     const int my_b = (nbi > wave) ? (nbi - wave + SK_NW - 1) / SK_NW : 0;     // ... of which this wave issues my_b
     const uint16_t *bp[SK_BL];
     bool bok[SK_BL];
@@ -105,7 +127,19 @@ __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, co
         const int u = (wave + SK_NW * jj) * 8 + lrow;
         bchunk[jj] = (lane & 7) ^ ((u >> 1) & 7);
         bok[jj] = u < brows;
-        bp[jj] = Bm + (int64_t)(bok[jj] ? u : 0) * C + (int64_t)st0 * SK_BK + bchunk[jj] * 8;
+        if constexpr (GROUP) {
+            // the 8 rows of an instruction lie in one projection's block (blocks are multiples of 16 rows)
+            int first = 0, cum = 0;
+            const uint16_t *base = gv.small[0] + p_at[0];
+#pragma unroll
+            for (int p = 1; p < kMaxGroup; ++p) {
+                cum += p_r16[p - 1];
+                if (p < gv.n_proj && u >= cum) { first = cum; base = gv.small[p] + p_at[p]; }
+            }
+            bp[jj] = base + (int64_t)(bok[jj] ? u - first : 0) * C + (int64_t)st0 * SK_BK + bchunk[jj] * 8;
+        } else {
+            bp[jj] = Bm + (int64_t)(bok[jj] ? u : 0) * C + (int64_t)st0 * SK_BK + bchunk[jj] * 8;
+        }
     }
     const int lps = SK_XL + my_b;                                     // loads per stage issued by this wave
 
@@ -186,7 +220,7 @@ __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, co
             if (b < nb) {
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
-                    dst[((wave * SK_MB + mb) * 16 + kg * 4 + i) * g.r16 + b * 16 + lm] = acc[mb][b][i];
+                    dst[((wave * SK_MB + mb) * 16 + kg * 4 + i) * r16 + b * 16 + lm] = acc[mb][b][i];
             }
 }
 
@@ -194,9 +228,13 @@ __global__ void __launch_bounds__(64 * SK_NW) k_skinny(MetaView mv, int mode, co
 //   hf fp32 [len][r]   (mode 0: the activation itself; mode 1: scaled by scale_k)
 //   hb bf16 [len][rp]  scale_k * sum, zero beyond r           (K-extension operand of the GEMM)
 //   zt bf16 [r16][lp]  transposed, zero for padding tokens and rows >= r; scaled if zt_scaled
+// GROUP: the partial tiles are those of a fused pass (pitch = the fused rank of the segment's adapter); mv is the view of
+// projection `proj`, whose columns start behind those of the projections before it.
+template <bool GROUP>
 __global__ void __launch_bounds__(256) k_skinny_finish(MetaView mv, int mode, const float *__restrict__ part,
                                                       int n_split, float *__restrict__ hf, uint16_t *__restrict__ hb,
-                                                      uint16_t *__restrict__ zt, int zt_scaled)
+                                                      uint16_t *__restrict__ zt, int zt_scaled,
+                                                      std::conditional_t<GROUP, GroupView, NoGroup> gv, int proj)
 {
     constexpr int FR = 16;                            // token rows per workgroup (grid.y slices of a block)
     __shared__ float tile[FR * PLORA_MAX_RANK];       // [FR][r16], pitch r16
@@ -210,17 +248,40 @@ __global__ void __launch_bounds__(256) k_skinny_finish(MetaView mv, int mode, co
     nt = nt < 0 ? 0 : (nt < FR ? nt : FR);
     if (t0 >= g.lp) return;                           // slice lies past the padded segment: nothing to write
     const int r = g.r, r16 = g.r16;
-    const int64_t tile_elems = (int64_t)kSkinnyRows * mv.hdr->max_r16;
-    const int64_t split_stride = (int64_t)gridDim.x * tile_elems;
-    // the FR rows of r16 partial sums are contiguous in every split: flat walk, four floats per thread
-    const float4 *src = reinterpret_cast<const float4 *>(part + (int64_t)blk * tile_elems + (int64_t)r0 * r16);
-    for (int e = threadIdx.x; e < FR * r16 / 4; e += 256) {
-        float4 sum = src[e];
-        for (int sp = 1; sp < n_split; ++sp) {        // fixed order
-            const float4 v = src[sp * (split_stride / 4) + e];
-            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+    if constexpr (GROUP) {
+        int pitch = 0, col0 = 0;
+        for (int p = 0; p < gv.n_proj; ++p) {
+            const int rp16 = gv.mv[p].ad[g.adapter].r16;
+            if (p < proj) col0 += rp16;
+            pitch += rp16;
         }
-        reinterpret_cast<float4 *>(tile)[e] = sum;
+        const int64_t tile_elems = (int64_t)kSkinnyRows * gv.max_r16;
+        const int64_t split_stride = (int64_t)gridDim.x * tile_elems;
+        const float *src = part + (int64_t)blk * tile_elems + (int64_t)r0 * pitch + col0;
+        const int q = r16 / 4;                        // float4 per row of this projection's columns
+        for (int e = threadIdx.x; e < FR * q; e += 256) {
+            const int row = e / q, c4 = e - row * q;
+            const float *s0 = src + row * pitch + c4 * 4;
+            float4 sum = *reinterpret_cast<const float4 *>(s0);
+            for (int sp = 1; sp < n_split; ++sp) {    // fixed order
+                const float4 v = *reinterpret_cast<const float4 *>(s0 + sp * split_stride);
+                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            }
+            reinterpret_cast<float4 *>(tile)[e] = sum;
+        }
+    } else {
+        const int64_t tile_elems = (int64_t)kSkinnyRows * mv.hdr->max_r16;
+        const int64_t split_stride = (int64_t)gridDim.x * tile_elems;
+        // the FR rows of r16 partial sums are contiguous in every split: flat walk, four floats per thread
+        const float4 *src = reinterpret_cast<const float4 *>(part + (int64_t)blk * tile_elems + (int64_t)r0 * r16);
+        for (int e = threadIdx.x; e < FR * r16 / 4; e += 256) {
+            float4 sum = src[e];
+            for (int sp = 1; sp < n_split; ++sp) {        // fixed order
+                const float4 v = src[sp * (split_stride / 4) + e];
+                sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+            }
+            reinterpret_cast<float4 *>(tile)[e] = sum;
+        }
     }
     __syncthreads();
     // outputs: thread -> (token tt = tid / 16, columns j = tid % 16 + 16 m), or transposed for zt
@@ -267,17 +328,42 @@ hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode,
     const int per = (n_stage_all + n_split - 1) / n_split;
     const size_t lds = (size_t)SK_NST * (SK_XT + h.max_r16 * SK_BK * 2);
     {
-        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(k_skinny), 0);
+        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(k_skinny<false>), 0);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(k_skinny, dim3((unsigned)h.n_blocks, (unsigned)n_split), dim3(64 * SK_NW), lds, st, mv, mode,
+    hipLaunchKernelGGL(k_skinny<false>, dim3((unsigned)h.n_blocks, (unsigned)n_split), dim3(64 * SK_NW), lds, st, mv, mode,
                        static_cast<const uint16_t *>(S), (int)C, static_cast<const uint16_t *>(at),
-                       static_cast<const uint16_t *>(zero), part, per);
+                       static_cast<const uint16_t *>(zero), part, per, NoGroup{0});
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_skinny_finish, dim3((unsigned)h.n_blocks, kSkinnyRows / 16), dim3(256), 0, st, mv, mode, part, n_split, hf,
-                       static_cast<uint16_t *>(hb), static_cast<uint16_t *>(zt), zt_scaled ? 1 : 0);
+    hipLaunchKernelGGL(k_skinny_finish<false>, dim3((unsigned)h.n_blocks, kSkinnyRows / 16), dim3(256), 0, st, mv, mode, part, n_split, hf,
+                       static_cast<uint16_t *>(hb), static_cast<uint16_t *>(zt), zt_scaled ? 1 : 0, NoGroup{0}, 0);
     return hipGetLastError();
+}
+
+hipError_t launch_skinny_group(const GroupView &gv, const MetaHeader &hv, const void *x, int64_t C, const void *zero, float *part,
+                               float *const *hf, void *const *hb, void *const *zt, hipStream_t st)
+{
+    if (hv.n_blocks == 0) return hipSuccess;
+    if (gv.n_proj < 2 || gv.n_proj > kMaxGroup || gv.max_r16 > PLORA_MAX_RANK || hv.max_r16 != gv.max_r16) return hipErrorInvalidValue;
+    const int n_split = skinny_splits(hv, C);
+    const int n_stage_all = (int)((C + SK_BK - 1) / SK_BK);
+    const int per = (n_stage_all + n_split - 1) / n_split;
+    const size_t lds = (size_t)SK_NST * (SK_XT + gv.max_r16 * SK_BK * 2);
+    {
+        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(k_skinny<true>), 7);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(k_skinny<true>, dim3((unsigned)hv.n_blocks, (unsigned)n_split), dim3(64 * SK_NW), lds, st, gv.mv[0], 0,
+                       static_cast<const uint16_t *>(x), (int)C, static_cast<const uint16_t *>(nullptr),
+                       static_cast<const uint16_t *>(zero), part, per, gv);
+    hipError_t e = hipGetLastError();
+    for (int p = 0; p < gv.n_proj && e == hipSuccess; ++p) {
+        hipLaunchKernelGGL(k_skinny_finish<true>, dim3((unsigned)hv.n_blocks, kSkinnyRows / 16), dim3(256), 0, st, gv.mv[p], 0, part,
+                           n_split, hf[p], static_cast<uint16_t *>(hb[p]), static_cast<uint16_t *>(zt[p]), 0, gv, p);
+        e = hipGetLastError();
+    }
+    return e;
 }
 
 }  // namespace plora

@@ -53,11 +53,15 @@ __device__ inline void tc_wait_vmcnt(int n)
 
 // grid (column tiles, adapters, token splits).  part != nullptr: write the fp32 partial tile
 // [r16][C] of this split instead of the final result.
-template <bool WANT_DA, int BC>
+// GROUP (dA only): the small factor of adapter k is the transposed g of several projections that share x, one below
+// the other (GroupView); mv is projection 0's view, `zt` is not used, every projection's dA_k gets its own columns.
+template <bool WANT_DA, int BC, bool GROUP = false>
 __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 2))) k_tokc(MetaView mv, const uint16_t *__restrict__ S, int C,
                                              const uint16_t *__restrict__ zt, const uint16_t *__restrict__ zero,
-                                             float *__restrict__ part, int r16_total, int nst)
+                                             float *__restrict__ part, int r16_total, int nst,
+                                             std::conditional_t<GROUP, GroupView, NoGroup> gv)
 {
+    static_assert(!GROUP || WANT_DA, "");
     // BC columns of the big matrix per workgroup (256 or 128), one wave per 32 columns
     static_assert(BC == 256 || BC == 128, "");
     constexpr int TC_BC = BC, TC_NW = BC / 32, TC_S_BYTES = TC_BT * BC * 2;
@@ -72,11 +76,24 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
     const int k = mv.ad[blockIdx.y].by_tokens;       // longest adapters first
     const AdapterInfo a = mv.ad[k];
     const int c0 = blockIdx.x * TC_BC;
-    const int nb = a.r16 / 16;
+    int r16 = a.r16, max_r16;
+    int p_r16[kMaxGroup];                            // GROUP: rank rows (padded to 16) of each projection
+    if constexpr (GROUP) {
+        r16 = 0;
+#pragma unroll
+        for (int p = 0; p < kMaxGroup; ++p) {
+            p_r16[p] = p < gv.n_proj ? gv.mv[p].ad[k].r16 : 0;
+            r16 += p_r16[p];
+        }
+        max_r16 = gv.max_r16;
+    } else {
+        max_r16 = mv.hdr->max_r16;
+    }
+    const int nb = r16 / 16;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const uint32_t lds_base = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)LDS_PTR(char, lds));
-    const int stage_bytes = TC_S_BYTES + mv.hdr->max_r16 * TC_BT * 2;
+    const int stage_bytes = TC_S_BYTES + max_r16 * TC_BT * 2;
 
     // steps (TC_BT tokens each) of this adapter over its own segments (list built on the host), and the
     // slice of them that belongs to this split
@@ -103,12 +120,35 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
         if (skip >= st_here) { skip -= st_here; ++cur_li; }
         else { cur_t = skip * TC_BT; skip = 0; }
     }
+    // GROUP: the 8 rows that small-factor load instruction q = wave + TC_NW jj covers lie in one projection: zp[jj], and
+    // zfirst[jj] is the first of that projection's rows in the fused factor
+    constexpr int ZL = (PLORA_MAX_RANK / TC_ZR + TC_NW - 1) / TC_NW;
+    int zp[ZL], zfirst[ZL];
+    if constexpr (GROUP) {
+#pragma unroll
+        for (int jj = 0; jj < ZL; ++jj) {
+            const int u = (wave + TC_NW * jj) * TC_ZR;
+            int cum = 0;
+            zp[jj] = 0; zfirst[jj] = 0;
+#pragma unroll
+            for (int p = 1; p < kMaxGroup; ++p) {
+                cum += p_r16[p - 1];
+                if (p < gv.n_proj && u >= cum) { zp[jj] = p; zfirst[jj] = cum; }
+            }
+        }
+    }
     int seg_row0 = 0, seg_len = 0, seg_lp = 0;
     int64_t seg_zt = 0;
+    const uint16_t *seg_zp[ZL];                      // GROUP: start of the current segment's rows in projection zp[jj]'s buffer
     auto load_desc = [&]() {
         if (cur_li < n_own) {
-            const SegInfo g = mv.seg[own[cur_li]];
+            const int sidx = own[cur_li];
+            const SegInfo g = mv.seg[sidx];
             seg_row0 = g.row0; seg_len = g.row1 - g.row0; seg_lp = g.lp; seg_zt = g.zt_off;
+            if constexpr (GROUP) {
+#pragma unroll
+                for (int jj = 0; jj < ZL; ++jj) seg_zp[jj] = gv.small[zp[jj]] + gv.mv[zp[jj]].seg[sidx].zt_off;
+            }
         }
     };
     load_desc();
@@ -118,7 +158,7 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
     // Small-factor tile [r16 j][TC_ZC chunks]:
     // instruction q covers rows TC_ZR q.., lane -> (row TC_ZR q + lane/TC_ZC, slot lane%TC_ZC), slot c' of
     // row u holds chunk c' ^ ((u >> TC_ZSH) & (TC_ZC-1)); wave w issues q = w, w + TC_NW, ... below r16/TC_ZR.
-    const int nzi = a.r16 / TC_ZR;
+    const int nzi = r16 / TC_ZR;
     const int my_z = (nzi > wave) ? (nzi - wave + TC_NW - 1) / TC_NW : 0;
     const int lps = TC_SL + my_z;
     auto load16 = [&](const uint16_t *gp, uint32_t dst) {
@@ -144,7 +184,8 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
                 const int q = wave + TC_NW * jj;
                 const int u = q * TC_ZR + lane / TC_ZC;
                 const int chunk = (lane % TC_ZC) ^ ((u >> TC_ZSH) & (TC_ZC - 1));
-                load16(zt + seg_zt + (int64_t)u * seg_lp + tbase + chunk * 8, base + TC_S_BYTES + q * 1024);
+                if constexpr (GROUP) load16(seg_zp[jj] + (int64_t)(u - zfirst[jj]) * seg_lp + tbase + chunk * 8, base + TC_S_BYTES + q * 1024);
+                else load16(zt + seg_zt + (int64_t)u * seg_lp + tbase + chunk * 8, base + TC_S_BYTES + q * 1024);
             }
         }
         cur_t = tbase + TC_BT;
@@ -226,6 +267,11 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
 
     // ---- epilogue.  Lane holds rank column j = 16b + i16 and big-matrix columns c = cbase + 4*kg + i.
     const float mult = WANT_DA ? 1.f : a.scale;
+    int r16_off = a.r16_off;
+    if constexpr (GROUP) {
+        r16_off = 0;                                  // rows of the fused factors of the adapters before this one
+        for (int p = 0; p < gv.n_proj; ++p) r16_off += gv.mv[p].ad[k].r16_off;
+    }
 #pragma unroll
     for (int cb = 0; cb < TC_CB; ++cb) {
         const int c = c0 + wave * (TC_CB * 16) + cb * 16 + kg * 4;
@@ -236,7 +282,20 @@ __global__ void __launch_bounds__(2 * BC) __attribute__((amdgpu_waves_per_eu(2, 
                 if (part) {
                     float4 v;
                     v.x = acc[cb][b][0]; v.y = acc[cb][b][1]; v.z = acc[cb][b][2]; v.w = acc[cb][b][3];
-                    *reinterpret_cast<float4 *>(part + ((int64_t)blockIdx.z * r16_total + a.r16_off + j) * C + c) = v;
+                    *reinterpret_cast<float4 *>(part + ((int64_t)blockIdx.z * r16_total + r16_off + j) * C + c) = v;
+                } else if constexpr (GROUP) {
+                    int pj = 0, first = 0, cum = 0;   // the projection that owns rank block b, and its first row
+#pragma unroll
+                    for (int p = 1; p < kMaxGroup; ++p) {
+                        cum += p_r16[p - 1];
+                        if (p < gv.n_proj && b * 16 >= cum) { pj = p; first = cum; }
+                    }
+                    const AdapterInfo ap = gv.mv[pj].ad[k];
+                    const int jl = j - first;
+                    if (jl < ap.r) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) ap.dA[(int64_t)(c + i) * ap.r + jl] = acc[cb][b][i];
+                    }
                 } else if (j < a.r) {
                     if (WANT_DA) {
 #pragma unroll
@@ -277,6 +336,31 @@ __global__ void __launch_bounds__(256) k_tokc_finish(MetaView mv, const float *_
     for (int sp = 1; sp < kTokMaxSplits; ++sp) sum += v[sp];
     if (WANT_DA) a.dA[(int64_t)c * a.r + j] = sum;
     else a.dB[(int64_t)j * C + c] = a.scale * sum;
+}
+
+// The same for the partial tiles of a fused dA pass: row -> adapter -> projection -> that projection's dA_k.
+__global__ void __launch_bounds__(256) k_tokc_finish_group(GroupView gv, const float *__restrict__ part, int C, int n_split)
+{
+    const int row = blockIdx.y;                      // row of the concatenated [r16_total][C] partial tile
+    const int n_ad = gv.mv[0].hdr->n_adapters;
+    int k = 0, k_off = 0;
+    for (int q = 0; q < n_ad; ++q) {
+        int off = 0;
+        for (int p = 0; p < gv.n_proj; ++p) off += gv.mv[p].ad[q].r16_off;
+        if (row >= off) { k = q; k_off = off; }
+    }
+    int j = row - k_off, pj = 0;                     // row inside the fused factor of adapter k -> projection, local row
+    for (; pj < gv.n_proj - 1; ++pj) {
+        const int r16 = gv.mv[pj].ad[k].r16;
+        if (j < r16) break;
+        j -= r16;
+    }
+    const AdapterInfo a = gv.mv[pj].ad[k];
+    const int c = blockIdx.x * 256 + threadIdx.x;
+    if (j >= a.r || c >= C) return;
+    float sum = part[(int64_t)row * C + c];
+    for (int sp = 1; sp < n_split; ++sp) sum += part[((int64_t)sp * gv.r16_total + row) * C + c];   // fixed order
+    a.dA[(int64_t)c * a.r + j] = sum;
 }
 
 // Launch shape: column-tile width and number of token splits.  128-column tiles throughout: two workgroups then
@@ -335,7 +419,36 @@ static hipError_t launch_tokc(const MetaView &mv, const MetaHeader &h, const uin
         if (e != hipSuccess) return e;
     }
     const dim3 grid((unsigned)((C + BC - 1) / BC), (unsigned)h.n_adapters, (unsigned)n_split);
-    hipLaunchKernelGGL(kern, grid, dim3(2 * BC), lds, st, mv, S, C, zt, zero, n_split > 1 ? part : nullptr, r16_total, nst);
+    hipLaunchKernelGGL(kern, grid, dim3(2 * BC), lds, st, mv, S, C, zt, zero, n_split > 1 ? part : nullptr, r16_total, nst, NoGroup{0});
+    return hipGetLastError();
+}
+
+hipError_t launch_tokc_group_dA(const GroupView &gv, const MetaHeader &hv, const void *x, int64_t C, const void *zero,
+                                float *part, int n_split, int n_active_adapters, hipStream_t st)
+{
+    if (hv.n_adapters == 0) return hipSuccess;
+    if (gv.n_proj < 2 || gv.n_proj > kMaxGroup || gv.max_r16 > PLORA_MAX_RANK || hv.max_r16 != gv.max_r16) return hipErrorInvalidValue;
+    int bc = 128;
+    if (tokc_plan(hv, C, n_active_adapters, &bc) != n_split || bc != 128) return hipErrorInvalidValue;
+    constexpr int BC = 128;
+    const size_t stage = (size_t)TC_BT * BC * 2 + (size_t)(gv.max_r16 > 0 ? gv.max_r16 : 16) * TC_BT * 2;
+    size_t budget = (size_t)TC_LDS_BYTES * BC / 256;
+    if (budget < 2 * stage) budget = 2 * stage;
+    int nst = (int)(budget / stage);
+    nst = nst > TC_MAX_NST ? TC_MAX_NST : nst;
+    auto kern = k_tokc<true, BC, true>;
+    {
+        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(kern), 8);
+        if (e != hipSuccess) return e;
+    }
+    const dim3 grid((unsigned)((C + BC - 1) / BC), (unsigned)hv.n_adapters, (unsigned)n_split);
+    hipLaunchKernelGGL(kern, grid, dim3(2 * BC), nst * stage, st, gv.mv[0], static_cast<const uint16_t *>(x), (int)C,
+                       static_cast<const uint16_t *>(nullptr), static_cast<const uint16_t *>(zero), n_split > 1 ? part : nullptr,
+                       gv.r16_total, nst, gv);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || n_split <= 1) return e;
+    hipLaunchKernelGGL(k_tokc_finish_group, dim3((unsigned)((C + 255) / 256), (unsigned)gv.r16_total), dim3(256), 0, st, gv, part,
+                       (int)C, n_split);
     return hipGetLastError();
 }
 

@@ -28,7 +28,8 @@ EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_work
            "plora_build_metadata", "plora_linear_fwd", "plora_linear_fwd_noalloc", "plora_linear_bwd",
            "plora_set_kernel_timing", "plora_kernel_time", "plora_debug_metadata", "plora_adamw_step",
            "plora_lora_workspace_bytes", "plora_lora_fwd", "plora_lora_bwd",
-           "plora_nf4_workspace_bytes", "plora_nf4_dequantize", "plora_linear_fwd_nf4", "plora_linear_bwd_nf4"]
+           "plora_nf4_workspace_bytes", "plora_nf4_dequantize", "plora_linear_fwd_nf4", "plora_linear_bwd_nf4",
+           "plora_group_workspace_bytes", "plora_group_fwd", "plora_group_bwd"]
 
 
 class PloraError(RuntimeError):
@@ -42,6 +43,10 @@ class plora_desc(C.Structure):
                 ("n_seg", C.c_int32), ("n_adapters", C.c_int32),
                 ("seg_off", C.c_void_p), ("seg_adapter", C.c_void_p),
                 ("rank", C.c_void_p), ("scale", C.c_void_p), ("dtype", C.c_int32), ("w_layout", C.c_int32)]
+
+
+class plora_group(C.Structure):
+    _fields_ = [("n_proj", C.c_int32), ("desc", C.POINTER(plora_desc))]
 
 
 class plora_adamw_hparams(C.Structure):
@@ -119,6 +124,12 @@ def lib():
         L.plora_linear_fwd_nf4.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 8 + [C.c_size_t, C.c_void_p]
         L.plora_linear_bwd_nf4.restype = C.c_int
         L.plora_linear_bwd_nf4.argtypes = [C.POINTER(plora_desc)] + [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
+        L.plora_group_workspace_bytes.restype = C.c_size_t
+        L.plora_group_workspace_bytes.argtypes = [C.POINTER(plora_group)]
+        L.plora_group_fwd.restype = C.c_int
+        L.plora_group_fwd.argtypes = [C.POINTER(plora_group)] + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
+        L.plora_group_bwd.restype = C.c_int
+        L.plora_group_bwd.argtypes = [C.POINTER(plora_group)] + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
         L.plora_set_kernel_timing.restype = None
         L.plora_set_kernel_timing.argtypes = [C.c_int]
         L.plora_kernel_time.restype = C.c_int
@@ -295,6 +306,68 @@ def plora_lora_bwd(d: Desc, x, A: Sequence, B: Sequence, dy, h_saved, dx, dA: Op
     kdb, pdb = _ptr_table(dB)
     _check(lib().plora_lora_bwd(d.ref, _ptr(x), pa, pb, _ptr(dy), _ptr(h_saved), _ptr(dx), pda, pdb, _ptr(workspace),
                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+class Group:
+    """Projections that read the same x; keeps the array of C descriptions (and the Desc objects behind it) alive."""
+
+    def __init__(self, descs: Sequence[Desc]):
+        self.descs = list(descs)
+        self.arr = (plora_desc * max(len(self.descs), 1))(*[d.c for d in self.descs])
+        self.c = plora_group(len(self.descs), self.arr)
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def _ptr_array(tensors: Optional[Sequence]):
+    """HOST array of device pointers (entries may be None)."""
+    if tensors is None:
+        return None, None
+    arr = (C.c_void_p * max(len(tensors), 1))(*[None if t is None else int(t.data_ptr()) for t in tensors])
+    return arr, C.cast(arr, C.c_void_p)
+
+
+def _table_array(tables: Optional[Sequence]):
+    """HOST array of HOST pointer tables (entries may be None)."""
+    if tables is None:
+        return None, None
+    keep = [_ptr_table(t) for t in tables]
+    arr = (C.c_void_p * max(len(tables), 1))(*[None if k[1] is None else k[1].value for k in keep])
+    return (keep, arr), C.cast(arr, C.c_void_p)
+
+
+def plora_group_workspace_bytes(g: Group) -> int:
+    return int(lib().plora_group_workspace_bytes(g.ref))
+
+
+def plora_group_fwd(g: Group, x, W: Sequence, A: Sequence[Sequence], B: Sequence[Sequence], y: Sequence,
+                    h_saved: Optional[Sequence], workspace, stream=None) -> None:
+    """Enqueues the forward of every projection of the group on one x (entry p of each list belongs to projection p)."""
+    kw, pw = _ptr_array(W)
+    ka, pa = _table_array(A)
+    kb, pb = _table_array(B)
+    ky, py = _ptr_array(y)
+    kh, ph = _ptr_array(h_saved)
+    _check(lib().plora_group_fwd(g.ref, _ptr(x), pw, pa, pb, py, ph, _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+def plora_group_bwd(g: Group, x, W: Sequence, A: Sequence[Sequence], B: Sequence[Sequence], dy: Sequence,
+                    h_saved: Optional[Sequence], dx: Optional[Sequence], dA: Optional[Sequence], dB: Optional[Sequence],
+                    workspace, stream=None) -> None:
+    """Enqueues the backward of every projection of the group (dx[p] is projection p's own input gradient)."""
+    kw, pw = _ptr_array(W)
+    ka, pa = _table_array(A)
+    kb, pb = _table_array(B)
+    kdy, pdy = _ptr_array(dy)
+    kh, ph = _ptr_array(h_saved)
+    kdx, pdx = _ptr_array(dx)
+    kda, pda = _table_array(dA)
+    kdb, pdb = _table_array(dB)
+    _check(lib().plora_group_bwd(g.ref, _ptr(x), pw, pa, pb, pdy, ph, pdx, pda, pdb, _ptr(workspace),
+                                 workspace.numel() * workspace.element_size(), _stream(stream)))
 
 
 def plora_nf4_workspace_bytes(d: Desc) -> int:

@@ -150,6 +150,46 @@ def brute_force_metadata(seg_off, seg_adapter, rank, block_rows):
     return np.array(h_off, dtype=np.int64), np.array(blocks, dtype=np.int32).reshape(-1, 4)
 
 
+def test_grouped_calls_reject_before_touching_the_device():
+    """Groups: 1 to PLORA_MAX_GROUP projections that agree in dtype, T, d_in and packing; everything else is free.  The
+    workspace holds every projection's own plus the fused passes' partial tiles."""
+    L = plora.lib()
+    a, b = mk(), mk(K=40, rank=(16, 3), scale=(0.5, 0.5), w_layout=1)
+    g = plora.Group([a, b])
+    gw = plora.plora_group_workspace_bytes(g)
+    assert gw > plora.plora_workspace_bytes(a) + plora.plora_workspace_bytes(b)
+    assert plora.plora_group_workspace_bytes(plora.Group([a])) >= plora.plora_workspace_bytes(a)
+    assert plora.plora_group_workspace_bytes(plora.Group([a] * 4)) > 0
+    assert plora.plora_status_string(11)
+    for bad in ([], [a] * 5, [a, mk(D=32)], [a, mk(dtype=plora.PLORA_F32)], [a, mk(seg_off=(0, 4, 8))],
+                [a, mk(seg_adapter=(1, 1))], [a, mk(T=9, seg_off=(0, 3, 9))],
+                [a, mk(rank=(4, 8, 2), scale=(1.0, 2.0, 1.0))]):
+        gb = plora.Group(bad)
+        assert plora.plora_group_workspace_bytes(gb) == 0, bad
+        assert L.plora_group_fwd(gb.ref, 0x1000, None, None, None, None, None, 0x1000, 1 << 30, None) == 11, bad
+    assert L.plora_group_fwd(plora.Group([a, mk(rank=(4, 300))]).ref, 0x1000, None, None, None, None, None, 0x1000, 1 << 30, None) == 5
+    assert L.plora_group_fwd(None, 0x1000, None, None, None, None, None, 0x1000, 1 << 30, None) == 1
+    tab = (C.c_void_p * 2)(0x1000, 0x2000)
+    tabp = C.cast(tab, C.c_void_p)
+    two = lambda v0, v1: C.cast((C.c_void_p * 2)(v0, v1), C.c_void_p)
+    keep = [two(0x1000, 0x2000), two(tabp.value, tabp.value), two(0x3000, 0x4000)]
+    Wp, ABp, yp = keep
+    fwd = lambda x, W, A, B, y, ws, n: L.plora_group_fwd(g.ref, x, W, A, B, y, None, ws, n, None)
+    assert fwd(0x1000, None, ABp, ABp, yp, 0x1000, gw) == 1
+    assert fwd(0x1000, Wp, None, ABp, yp, 0x1000, gw) == 1
+    assert fwd(0x1000, Wp, ABp, ABp, None, 0x1000, gw) == 1
+    assert fwd(None, Wp, ABp, ABp, yp, 0x1000, gw) == 1
+    assert fwd(0x1000, Wp, ABp, ABp, yp, 0x1000, gw - 1) == 7
+    assert fwd(0x1000, Wp, ABp, ABp, yp, 0x1010, gw) == 6
+    assert fwd(0x1000, Wp, ABp, ABp, two(0x3000, 0x4004), 0x1000, gw) == 6          # second projection's y misaligned
+    assert fwd(0x1000, Wp, ABp, ABp, two(0x3000, None), 0x1000, gw) == 1
+    bwd = lambda dy, dx, dA, dB: L.plora_group_bwd(g.ref, 0x1000, Wp, ABp, ABp, dy, None, dx, dA, dB, 0x1000, gw, None)
+    assert bwd(None, None, None, None) == 1
+    assert bwd(two(0x1000, None), None, None, None) == 1
+    assert bwd(yp, None, ABp, None) == 1                                          # dA without dB
+    assert bwd(yp, two(0x1000, 0x1008), None, None) == 6
+
+
 @pytest.mark.parametrize("seed", range(6))
 def test_metadata_equals_brute_force(seed):
     rng = np.random.default_rng(seed)
