@@ -54,6 +54,8 @@ def main():
                     help="storage of the frozen weight for the headline run: W[d_in][d_out] (default), W[d_out][d_in], or "
                          "both copies (forward reads [d_out][d_in], backward [d_in][d_out])")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
+    ap.add_argument("--grouped", action="store_true",
+                    help="with --config 4 --linear -1: q / k / v and gate / up as grouped calls (plora_group_fwd / _bwd)")
     ap.add_argument("--no-per-config", action="store_true", help="skip the per_config array (profiling runs)")
     ap.add_argument("--no-context", action="store_true", help="skip the ceilings and the vendor-GEMM context figures")
     ap.add_argument("--sequential", action="store_true",
@@ -238,22 +240,56 @@ def main():
         plora.plora_set_kernel_timing(False)
         return kern
 
-    if args.linear < 0:
-        # profiling mode: the linears of the configuration back to back, forward in order, backward in reverse
-        lins = wl.config(args.config)
-        runs = [Runner(l, None, seed=1000 * args.config + i) for i, l in enumerate(lins)]
-
-        def layer_step(i):
+    def layer_steps(runs):
+        """The seven linears of a decoder layer back to back, forward in order, backward in reverse: as seven plain
+        calls each way, and with the projections that share an input (q / k / v on the layer's input, gate / up on the
+        MLP's) as grouped calls.  The grouped calls use the first member's input sets as the shared x."""
+        def plain(i):
             for r in runs:
                 r.fwd(i)
             for r in reversed(runs):
                 r.bwd(i)
 
+        def group_of(idx):
+            rs = [runs[j] for j in idx]
+            g = plora.Group([r.desc for r in rs])
+            return g, torch.empty(plora.plora_group_workspace_bytes(g), dtype=torch.uint8, device="cuda"), rs
+
+        def gfwd(gr, i):
+            g, ws, rs = gr
+            plora.plora_group_fwd(g, rs[0].xs[i % rs[0].n_sets], [r.W for r in rs], [r.A for r in rs], [r.B for r in rs],
+                                  [r.y for r in rs], [r.h for r in rs], ws)
+
+        def gbwd(gr, i):
+            g, ws, rs = gr
+            plora.plora_group_bwd(g, rs[0].xs[i % rs[0].n_sets], [r.W_bwd for r in rs], [r.A for r in rs], [r.B for r in rs],
+                                  [r.dys[i % r.n_sets] for r in rs], [r.h for r in rs], [r.dx for r in rs],
+                                  [r.dA for r in rs], [r.dB for r in rs], ws)
+
+        if len(runs) != 7:
+            return plain, None
+        qkv, gate_up = group_of((0, 1, 2)), group_of((4, 5))
+
+        def grouped(i):
+            gfwd(qkv, i); runs[3].fwd(i); gfwd(gate_up, i); runs[6].fwd(i)
+            runs[6].bwd(i); gbwd(gate_up, i); runs[3].bwd(i); gbwd(qkv, i)
+
+        return plain, grouped
+
+    if args.linear < 0:
+        # profiling mode: the linears of the configuration back to back (--grouped: q / k / v and gate / up as grouped calls)
+        lins = wl.config(args.config)
+        runs = [Runner(l, None, seed=1000 * args.config + i) for i, l in enumerate(lins)]
+        plain_step, grouped_step = layer_steps(runs)
+        if args.grouped and grouped_step is None:
+            raise SystemExit("--grouped needs the seven linears of configuration 4")
+        layer_step = grouped_step if args.grouped else plain_step
         ms = timed(layer_step, args.steps, args.warmup)
         fl = sum(l.flops_fwd_bwd() for l in lins)
         print(json.dumps({"metric": "packed multi-LoRA layer fwd+bwd TFLOP/s", "value": round(fl / (ms * 1e-3) / 1e12, 2),
                           "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
-                          "config": {"workload": f"config {args.config}: all {len(lins)} linears in sequence"}}))
+                          "config": {"workload": f"config {args.config}: all {len(lins)} linears in sequence"
+                                                 + (", q/k/v and gate/up as grouped calls" if args.grouped else "")}}))
         return
 
     # ---- headline workload ---------------------------------------------------------------------
@@ -524,20 +560,23 @@ def main():
                     torch.cuda.empty_cache()
             if cfg == 4:
                 runs = [r for _, r, _ in entries]
-
-                def layer_step(i):
-                    for r in runs:
-                        r.fwd(i)
-                    for r in reversed(runs):
-                        r.bwd(i)
-
+                layer_step, grouped_step = layer_steps(runs)
                 ms4 = timed(layer_step, n_pc, 3)
+                ms4g = timed(grouped_step, n_pc, 3)
+                kp, kg = kernel_times(layer_step, n_pc), kernel_times(grouped_step, n_pc)
                 f4 = sum(l.flops_fwd_bwd() for l, _, _ in entries)
                 per_config.append({"workload": "config 4: the seven linears of a decoder layer (q,k,v,o,gate,up,down), forward "
                                                "in order then backward in reverse, one stream",
                                    "ms_per_step": round(ms4, 4), "tflops": round(f4 / (ms4 * 1e-3) / 1e12, 1),
                                    "tokens_per_s": round(entries[0][0].layout.T / (ms4 * 1e-3), 1),
                                    "graph_replay_ms_per_step": round(graph_ms(layer_step, min(r.n_sets for r in runs)), 4),
+                                   "grouped": {"ms_per_step": round(ms4g, 4), "tflops": round(f4 / (ms4g * 1e-3) / 1e12, 1),
+                                               "graph_replay_ms_per_step": round(graph_ms(grouped_step, min(r.n_sets for r in runs)), 4),
+                                               "ms_per_step_in_kernel": {k: {"plain_7_launches": round(7 * kp[k], 4),
+                                                                             "grouped_4_launches": round(4 * kg[k], 4)}
+                                                                         for k in ("shrink", "da") if kp.get(k) and kg.get(k)},
+                                               "note": "plora_group_fwd / _bwd for q,k,v (one x) and gate,up (one x): one "
+                                                       "shrink pass and one dA pass over x per group; o and down as plain calls"},
                                    "linears": [e for _, _, e in entries]})
                 del runs
                 for i in range(len(entries)):

@@ -155,3 +155,50 @@ def test_group_forward_is_bitwise_the_plain_call(case):
         nh = lins[p].layout.sum_Lr()
         assert torch.equal(ref.h[:nh], dps[p].h[:nh]), f"projection {p}: saved activation differs"
         assert torch.equal(ref.y, dps[p].y), f"projection {p}: y differs"
+
+
+@pytest.mark.parametrize("members", [(0, 1, 2), (4, 5)], ids=["q_k_v", "gate_up"])
+def test_config4_groups_full_size(members):
+    """The decoder layer's two groups at full size (16384 tokens, 16 adapters; q / k / v differ in width): every
+    element of h, dA_k and dB_k of every projection against the oracle, and y, dx and h bit for bit against the plain
+    calls on the same inputs (whose full-size parity has its own test)."""
+    import torch
+    import gpu_harness as gh
+    import fullsize_checks as fc
+    from paper_2508_02932_amd import plora
+    lins = [wl.config(4)[i] for i in members]
+    print(f"[case] config 4 group {[l.name for l in lins]}", flush=True)
+    sys.stdout.flush()
+    tens = [l.tensors() for l in lins]
+    for t in tens[1:]:
+        t.x = tens[0].x
+    dps = [gh.upload(l, t, 0) for l, t in zip(lins, tens)]
+    group = plora.Group([dp.desc for dp in dps])
+    ws = torch.empty(plora.plora_group_workspace_bytes(group), dtype=torch.uint8, device="cuda")
+    x = dps[0].x
+    plora.plora_group_fwd(group, x, [dp.W for dp in dps], [dp.A for dp in dps], [dp.B for dp in dps], [dp.y for dp in dps],
+                          [dp.h for dp in dps], ws)
+    plora.plora_group_bwd(group, x, [dp.W for dp in dps], [dp.A for dp in dps], [dp.B for dp in dps], [dp.dy for dp in dps],
+                          None, [dp.dx for dp in dps], [dp.dA for dp in dps], [dp.dB for dp in dps], ws)
+    torch.cuda.synchronize()
+    for p, (lin, t, dp) in enumerate(zip(lins, tens, dps)):
+        gh.check_guards(dp)
+        lay = lin.layout
+        prob = make_problem(oracle, lin, t)
+        h_o = oracle.matmul.low_rank_activation(prob)
+        dA_o, dB_o = oracle.matmul.low_rank_gradients(prob, t.dy)
+        errs = {"h": fc.compare(gh.ragged_h_to_rows(lin, gh.to_np(dp.h)), h_o)}
+        for k in range(lay.n_adapters):
+            errs[f"dA{k}"] = fc.compare(gh.to_np(dp.dA[k]), dA_o[k])
+            errs[f"dB{k}"] = fc.compare(gh.to_np(dp.dB[k]), dB_o[k])
+        worst = max(errs.values())
+        print(f"  {lin.name}: max error over {len(errs)} tensors {worst:.2e}", flush=True)
+        assert all(np.isfinite(v) and v <= TOL["bf16"] for v in errs.values()), (lin.name, errs)
+        ref = gh.upload(lin, t, 0)
+        gh.forward(ref)
+        gh.backward(ref, use_saved_h=False)
+        torch.cuda.synchronize()
+        nh = lay.sum_Lr()
+        assert torch.equal(ref.h[:nh], dp.h[:nh]) and torch.equal(ref.y, dp.y) and torch.equal(ref.dx, dp.dx), lin.name
+        del ref
+        torch.cuda.empty_cache()
