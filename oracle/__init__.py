@@ -10,10 +10,11 @@ cases of appendix C.2), both computing in fp64:
 
 ``adamw`` holds the per-adapter optimizer step that follows the backward pass (fp64, element by
 element).  ``nf4`` holds the 4-bit storage format of a quantised base weight (the layer on such a
-weight is the layer above on its dequantised values).
+weight is the layer above on its dequantised values).  ``planner`` holds the scheduling side of the
+paper (memory model, packing of one job by enumeration, DTM, job planner, tail bound).
 
 Nothing here imports, or is imported by, the HIP library or its binding.  Only the tests, the
 smoke check and the benchmark's ``cpu_baseline`` leg may use this package.
 """
 from .problem import Problem  # noqa: F401
-from . import adamw, loops, matmul, nf4  # noqa: F401
+from . import adamw, loops, matmul, nf4, planner  # noqa: F401
