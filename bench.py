@@ -115,7 +115,7 @@ def main():
     class Runner:
         """One linear on the device with rotating input sets; step(i) = forward + backward."""
 
-        def __init__(self, lin, tensors=None, seed=0, w_layout=0):
+        def __init__(self, lin, tensors=None, seed=0, w_layout=0, max_sets=None):
             self.lin = lin
             lay = lin.layout
             # w_layout 2: the frozen weight is kept in both layouts and each direction gets the one whose contraction
@@ -131,6 +131,8 @@ def main():
             T, D, K = lay.T, lin.D, lin.K
             e = x.element_size()
             self.n_sets = max(1, -(-ROTATE_BYTES // max(min(T * D, T * K) * e, 1)))
+            if max_sets:
+                self.n_sets = min(self.n_sets, max_sets)
             self.xs = [x] + [x.clone() for _ in range(self.n_sets - 1)]
             self.dys = [dy] + [dy.clone() for _ in range(self.n_sets - 1)]
             self.W_bwd = W.t().contiguous() if w_layout == 1 else W      # [d_out][d_in] is the same matrix transposed in memory
@@ -530,6 +532,7 @@ def main():
 
     # ---- the other configurations -----------------------------------------------------------------
     per_config = None
+    layer_cost = None
     if not args.no_per_config:
         headline = (args.config, args.linear)
         del run
@@ -563,6 +566,16 @@ def main():
                 layer_step, grouped_step = layer_steps(runs)
                 ms4 = timed(layer_step, n_pc, 3)
                 ms4g = timed(grouped_step, n_pc, 3)
+                # the same layer on one configuration's own small batch (512 tokens, one adapter): with the full batch it
+                # gives the planner's cost model, time(tokens) = floor + slope * tokens
+                small_T = 512
+                small_runs = [Runner(wl.Linear(l.name + "_small", "bf16", l.D, l.K, wl.equal_layout(1, small_T, [16], [2.0]), 0.02,
+                                               wl.BASE_SEED + 4900 + j), None, seed=4900 + j, max_sets=8) for j, (l, _, _) in enumerate(entries)]
+                ms4s = timed(layer_steps(small_runs)[1], 4 * n_pc, 5)
+                del small_runs
+                slope = (ms4g - ms4s) / (entries[0][0].layout.T - small_T)
+                layer_cost = {"floor_ms": ms4s - slope * small_T, "ms_per_token": slope, "small_batch_tokens": small_T,
+                              "small_batch_ms": ms4s, "full_batch_tokens": entries[0][0].layout.T, "full_batch_ms": ms4g}
                 kp, kg = kernel_times(layer_step, n_pc), kernel_times(grouped_step, n_pc)
                 f4 = sum(l.flops_fwd_bwd() for l, _, _ in entries)
                 per_config.append({"workload": "config 4: the seven linears of a decoder layer (q,k,v,o,gate,up,down), forward "
@@ -648,6 +661,42 @@ def main():
                          + ("the whole step, nothing extrapolated" if whole else
                             "whole step extrapolated: row part scaled by T / rows, weight gradients by sum(L r)")}
 
+    # context leg (host only, not the metric): the packing planner on a search space of the paper's size, its cost
+    # model filled from the decoder-layer times measured above
+    planner = None
+    if layer_cost is not None:
+        rng = np.random.default_rng(120)
+        n_cfg, n_gpus_plan, n_layers, iters, seq = 120, 8, 32, 1000, 512
+        ranks = rng.choice([8, 16, 32, 64, 128], n_cfg)
+        batch = rng.choice([1, 2, 4, 8], n_cfg)
+        tokens = batch * seq
+        model = dict(n_layers=n_layers, hidden=4096, kv_hidden=1024, inter=14336, c_prec=2.0, c_grad=3.0)
+        mem = np.array([plora.plora_plan_lora_bytes(model, dict(rank=int(r), batch=int(b_), seq=seq, targets=127))
+                        for r, b_ in zip(ranks, batch)])
+        # the base model's activations kept for the backward pass grow with the packed tokens as well: charged to the configuration
+        mem = mem + tokens * (4096 * 16 + 14336 * 3) * 2.0 * n_layers
+        per_iter = n_layers * 1e-3                                          # ms of one layer -> seconds of all layers
+        eff = [2 ** i * 0.9 ** i for i in range(4)]                          # assumed speed-up of 2^i GPUs (one GPU here)
+        t_base = [60.0 + iters * per_iter * max(layer_cost["floor_ms"], 0.0) / e for e in eff]
+        t_cfg = np.array([iters * per_iter * layer_cost["ms_per_token"] * tokens / e for e in eff])
+        prob = plora.PlanProblem(ranks, mem, 16.1e9, 288.0e9, 0.9, t_base, t_cfg)
+        t0p = time.perf_counter()
+        sched = plora.plora_plan_schedule(prob, n_gpus_plan)
+        plan_ms = (time.perf_counter() - t0p) * 1e3
+        alone = float(sum(t_base[0] + t_cfg[0][k] for k in range(n_cfg))) / n_gpus_plan
+        planner = {"configs": n_cfg, "gpus": n_gpus_plan, "planning_ms": round(plan_ms, 2), "jobs": len(sched["jobs"]),
+                   "makespan_s": round(sched["makespan"], 1), "work_over_gpus_s": round(sched["gpu_work"] / n_gpus_plan, 1),
+                   "tail_bound": round(sched["tail_bound"], 4), "all_packings_proved_optimal": sched["all_proved"],
+                   "one_configuration_per_job_s": round(alone, 1),
+                   "speedup_over_one_configuration_per_job": round(alone / sched["makespan"], 3),
+                   "layer_cost_model": {k: round(v, 6) for k, v in layer_cost.items()},
+                   "note": "plora_plan_schedule (DTM + job planner) on 120 synthetic configurations (ranks 8-128, batches of 1-8 "
+                           "sequences of 512 tokens, 1000 iterations, 8B-shaped model of 32 layers, 8 GPUs of 288 GB).  Cost model: "
+                           "iteration = 32 x (floor + slope x packed tokens) from the two decoder-layer timings above, 60 s per job "
+                           "to load the model, parallel speed-up 1.8 per doubling ASSUMED (one GPU here); memory from the appendix-B "
+                           "model plus the base activations of the packed tokens.  one_configuration_per_job_s: the same 120 "
+                           "runs unpacked, one GPU each, spread evenly over the 8 GPUs"}
+
     out = {
         "metric": "packed multi-LoRA layer fwd+bwd TFLOP/s",
         "value": round(flops / (ms_per_step * 1e-3) / 1e12, 2),
@@ -674,6 +723,7 @@ def main():
         "vendor_gemm": vendor,
         "sequential_adapters": sequential,
         "per_config": per_config,
+        "planner": planner,
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))

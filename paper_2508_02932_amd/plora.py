@@ -29,7 +29,8 @@ EXPORTS = ["plora_status_string", "plora_validate", "plora_h_elems", "plora_work
            "plora_set_kernel_timing", "plora_kernel_time", "plora_debug_metadata", "plora_adamw_step",
            "plora_lora_workspace_bytes", "plora_lora_fwd", "plora_lora_bwd",
            "plora_nf4_workspace_bytes", "plora_nf4_dequantize", "plora_linear_fwd_nf4", "plora_linear_bwd_nf4",
-           "plora_group_workspace_bytes", "plora_group_fwd", "plora_group_bwd"]
+           "plora_group_workspace_bytes", "plora_group_fwd", "plora_group_bwd",
+           "plora_plan_lora_bytes", "plora_plan_pack", "plora_plan_dtm", "plora_plan_schedule"]
 
 
 class PloraError(RuntimeError):
@@ -47,6 +48,35 @@ class plora_desc(C.Structure):
 
 class plora_group(C.Structure):
     _fields_ = [("n_proj", C.c_int32), ("desc", C.POINTER(plora_desc))]
+
+
+class plora_plan_model(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("hidden", C.c_int64), ("kv_hidden", C.c_int64), ("inter", C.c_int64),
+                ("c_prec", C.c_double), ("c_grad", C.c_double)]
+
+
+class plora_plan_lora(C.Structure):
+    _fields_ = [("rank", C.c_int32), ("batch", C.c_int32), ("seq", C.c_int32), ("targets", C.c_uint32)]
+
+
+class plora_plan_sharding(C.Structure):
+    _fields_ = [("zero_level", C.c_int32), ("d_tp", C.c_int32), ("d_pp", C.c_int32), ("d_fsdp", C.c_int32)]
+
+
+class plora_plan_problem(C.Structure):
+    _fields_ = [("n_configs", C.c_int32), ("n_degrees", C.c_int32), ("rank", C.c_void_p), ("mem", C.c_void_p),
+                ("mem_base", C.c_double), ("mem_gpu", C.c_double), ("load", C.c_double),
+                ("t_base", C.c_void_p), ("t_config", C.c_void_p)]
+
+
+class plora_plan_job(C.Structure):
+    _fields_ = [("first", C.c_int32), ("count", C.c_int32), ("gpus", C.c_int32), ("proved", C.c_int32),
+                ("value", C.c_double), ("start", C.c_double), ("end", C.c_double)]
+
+
+class plora_plan_summary(C.Structure):
+    _fields_ = [("makespan", C.c_double), ("gpu_work", C.c_double), ("tail_bound", C.c_double),
+                ("n_jobs", C.c_int32), ("n_unscheduled", C.c_int32), ("all_proved", C.c_int32)]
 
 
 class plora_adamw_hparams(C.Structure):
@@ -130,6 +160,16 @@ def lib():
         L.plora_group_fwd.argtypes = [C.POINTER(plora_group)] + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
         L.plora_group_bwd.restype = C.c_int
         L.plora_group_bwd.argtypes = [C.POINTER(plora_group)] + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
+        L.plora_plan_lora_bytes.restype = C.c_double
+        L.plora_plan_lora_bytes.argtypes = [C.POINTER(plora_plan_model), C.POINTER(plora_plan_lora), C.POINTER(plora_plan_sharding)]
+        L.plora_plan_pack.restype = C.c_int
+        L.plora_plan_pack.argtypes = [C.POINTER(plora_plan_problem), C.c_int32, C.c_void_p, C.c_void_p, C.POINTER(plora_plan_job)]
+        L.plora_plan_dtm.restype = C.c_int
+        L.plora_plan_dtm.argtypes = [C.POINTER(plora_plan_problem), C.c_int32, C.c_void_p, C.c_void_p, C.c_int32,
+                                     C.POINTER(C.c_int32), C.c_void_p]
+        L.plora_plan_schedule.restype = C.c_int
+        L.plora_plan_schedule.argtypes = [C.POINTER(plora_plan_problem), C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                          C.POINTER(plora_plan_summary)]
         L.plora_set_kernel_timing.restype = None
         L.plora_set_kernel_timing.argtypes = [C.c_int]
         L.plora_kernel_time.restype = C.c_int
@@ -368,6 +408,73 @@ def plora_group_bwd(g: Group, x, W: Sequence, A: Sequence[Sequence], B: Sequence
     kdb, pdb = _table_array(dB)
     _check(lib().plora_group_bwd(g.ref, _ptr(x), pw, pa, pb, pdy, ph, pdx, pda, pdb, _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream)))
+
+
+# ---- packing planner (host only) --------------------------------------------------------------------------
+
+class PlanProblem:
+    """Host-side planner input; keeps the numpy arrays the C struct points at alive.  t_config is [n_degrees][n]."""
+
+    def __init__(self, rank, mem, mem_base: float, mem_gpu: float, load: float, t_base, t_config):
+        self.rank = np.ascontiguousarray(rank, dtype=np.int32)
+        self.mem = np.ascontiguousarray(mem, dtype=np.float64)
+        self.t_base = np.ascontiguousarray(t_base, dtype=np.float64)
+        self.t_config = np.ascontiguousarray(t_config, dtype=np.float64).reshape(len(self.t_base), len(self.rank))
+        self.c = plora_plan_problem(len(self.rank), len(self.t_base), self.rank.ctypes.data, self.mem.ctypes.data,
+                                    mem_base, mem_gpu, load, self.t_base.ctypes.data, self.t_config.ctypes.data)
+
+    @property
+    def ref(self):
+        return C.byref(self.c)
+
+
+def _jobs_to_py(jobs, n_jobs: int, cfg: np.ndarray):
+    return [{"configs": cfg[j.first:j.first + j.count].tolist(), "gpus": int(j.gpus), "value": float(j.value),
+             "proved": bool(j.proved), "start": float(j.start), "end": float(j.end)} for j in jobs[:n_jobs]]
+
+
+def _avail(p: PlanProblem, avail):
+    if avail is None:
+        return None, None
+    a = np.zeros(len(p.rank), dtype=np.uint8)
+    a[list(avail)] = 1
+    return a, a.ctypes.data
+
+
+def plora_plan_lora_bytes(model: dict, cfg: dict, sharding: Optional[dict] = None) -> float:
+    m = plora_plan_model(**model)
+    c = plora_plan_lora(**cfg)
+    s = plora_plan_sharding(**sharding) if sharding else None
+    return float(lib().plora_plan_lora_bytes(C.byref(m), C.byref(c), C.byref(s) if s else None))
+
+
+def plora_plan_pack(p: PlanProblem, degree_index: int, avail=None) -> dict:
+    """F(D, K) on the configurations listed in avail (None: all)."""
+    cfg = np.zeros(len(p.rank), dtype=np.int32)
+    job = plora_plan_job()
+    keep, ap = _avail(p, avail)
+    _check(lib().plora_plan_pack(p.ref, degree_index, ap, cfg.ctypes.data, C.byref(job)))
+    return _jobs_to_py([job], 1, cfg)[0]
+
+
+def plora_plan_dtm(p: PlanProblem, gpus: int, avail=None) -> list:
+    cfg = np.zeros(len(p.rank), dtype=np.int32)
+    jobs = (plora_plan_job * max(gpus, 1))()
+    n = C.c_int32(0)
+    keep, ap = _avail(p, avail)
+    _check(lib().plora_plan_dtm(p.ref, gpus, ap, C.cast(jobs, C.c_void_p), max(gpus, 1), C.byref(n), cfg.ctypes.data))
+    return _jobs_to_py(jobs, n.value, cfg)
+
+
+def plora_plan_schedule(p: PlanProblem, gpus: int) -> dict:
+    n = len(p.rank)
+    cfg = np.zeros(n, dtype=np.int32)
+    jobs = (plora_plan_job * n)()
+    s = plora_plan_summary()
+    _check(lib().plora_plan_schedule(p.ref, gpus, C.cast(jobs, C.c_void_p), n, cfg.ctypes.data, C.byref(s)))
+    return {"jobs": _jobs_to_py(jobs, s.n_jobs, cfg), "makespan": float(s.makespan), "gpu_work": float(s.gpu_work),
+            "tail_bound": float(s.tail_bound), "unscheduled": cfg[n - s.n_unscheduled:].tolist() if s.n_unscheduled else [],
+            "all_proved": bool(s.all_proved)}
 
 
 def plora_nf4_workspace_bytes(d: Desc) -> int:
