@@ -289,7 +289,8 @@ template <class Src> PLORA_HD void derive_phase1(const DescReader<Src> &in, cons
         a.r16 = pad_to(a.r, kRankPadMfma);
         a.scale = in.ad_scale(k);
         a.at_off = at; at += (int64_t)a.r16 * D;
-        a.ext_b = in.w_out_in() ? static_cast<const void *>(static_cast<const char *>(in.at_base()) + 2 * a.at_off) : a.B;
+        // (integer arithmetic: the host derives the tables with a null base, and an offset from a null pointer is undefined)
+        a.ext_b = in.w_out_in() ? reinterpret_cast<const void *>((uintptr_t)in.at_base() + 2 * (uintptr_t)a.at_off) : a.B;
         a.ap_off = ap; ap += (int64_t)a.rp * ap_rows;
         a.r16_off = r16_off; r16_off += a.r16;
         a.by_tokens = 0;                    // filled in by phase 2
