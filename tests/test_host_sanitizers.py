@@ -1,5 +1,5 @@
 """Sanitizer tier for the host code (no GPU): every source of libplora is compiled again with AddressSanitizer and
-UndefinedBehaviorSanitizer on its host side, linked with a small C++ driver (host_sanitize_driver.cpp) that walks
+UndefinedBehaviorSanitizer (and, in a second build, ThreadSanitizer with eight host threads) on its host side, linked with a small C++ driver (host_sanitize_driver.cpp) that walks
 random valid and broken descriptions through every host-only entry point, through the argument checks of the device
 entry points (each call fails its last check, so nothing is enqueued) and through the planner.  The run must end with
 "ok" and without a sanitizer report.  Device code is not instrumented (the sanitizers are host-only here)."""
@@ -18,26 +18,37 @@ HOST_SAN = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=unde
             "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
 
 
-@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not on PATH")
-def test_host_code_under_asan_and_ubsan():
+def build_and_run(san_compile, san_link, args, env_extra):
     work = tempfile.mkdtemp(prefix="plora_san_")
     try:
         with ThreadPoolExecutor(max_workers=8) as ex:
-            objs = list(ex.map(lambda s: build._compile(s, work, tuple(HOST_SAN)), build.SOURCES))
+            objs = list(ex.map(lambda s: build._compile(s, work, tuple(san_compile)), build.SOURCES))
         exe = os.path.join(work, "driver")
         drv = os.path.join(work, "driver.o")
-        cmd = ["hipcc", "--offload-arch=gfx950", "-std=c++17", "-O1", *HOST_SAN, "-I", os.path.join(ROOT, "include"),
+        cmd = ["hipcc", "--offload-arch=gfx950", "-std=c++17", "-O1", *san_compile, "-I", os.path.join(ROOT, "include"),
                "-c", os.path.join(ROOT, "tests", "host_sanitize_driver.cpp"), "-o", drv]
         res = subprocess.run(cmd, capture_output=True, text=True)
         assert res.returncode == 0, res.stderr[-3000:]
-        cmd = ["hipcc", "--offload-arch=gfx950", "-fsanitize=address", "-fsanitize=undefined", "-fno-gpu-sanitize", drv, *objs, "-o", exe]
+        cmd = ["hipcc", "--offload-arch=gfx950", *san_link, "-fno-gpu-sanitize", "-pthread", drv, *objs, "-o", exe]
         res = subprocess.run(cmd, capture_output=True, text=True)
         assert res.returncode == 0, res.stderr[-3000:]
-        env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0:abort_on_error=0:halt_on_error=1", UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1")
+        env = dict(os.environ, **env_extra)
         env.pop("LD_PRELOAD", None)
-        run = subprocess.run([exe, "300"], capture_output=True, text=True, env=env, timeout=600)
+        run = subprocess.run([exe, *args], capture_output=True, text=True, env=env, timeout=900)
         assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-4000:])
         assert run.stdout.strip().startswith("ok "), run.stdout
         assert "Sanitizer" not in run.stderr and "runtime error" not in run.stderr, run.stderr[-4000:]
     finally:
         shutil.rmtree(work, ignore_errors=True)
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not on PATH")
+def test_host_code_under_asan_and_ubsan():
+    build_and_run(HOST_SAN, ["-fsanitize=address", "-fsanitize=undefined"], ["300"],
+                  dict(ASAN_OPTIONS="detect_leaks=0:halt_on_error=1", UBSAN_OPTIONS="print_stacktrace=1:halt_on_error=1"))
+
+
+@pytest.mark.skipif(shutil.which("hipcc") is None, reason="hipcc not on PATH")
+def test_host_code_under_tsan_with_eight_threads():
+    tsan = ["-Xarch_host", "-fsanitize=thread", "-Xarch_host", "-fno-omit-frame-pointer", "-g"]
+    build_and_run(tsan, ["-fsanitize=thread"], ["60", "threads"], dict(TSAN_OPTIONS="halt_on_error=1:report_signal_unsafe=0"))
