@@ -13,7 +13,7 @@ What is computed (paper section 3.2, appendices A, B and D), written out plainly
   configurations; then time moves to the next job completion;
 * the bound of the tail effect (appendix D, the theorem on the approximation ratio).
 
-Readings where the paper leaves a choice (the design document lists them):
+Readings where the paper leaves a choice:
 
 * T(): "duration of a job, estimated with a cost model" that the paper does not print.  Here the
   caller supplies it in the form the packed execution has: for degree d = 2^i,
