@@ -15,11 +15,11 @@ What is computed (paper section 3.2, appendices A, B and D), written out plainly
 
 Readings where the paper leaves a choice:
 
-* T(): "duration of a job, estimated with a cost model" that the paper does not print.  Here the
-  caller supplies it in the form the packed execution has: for degree d = 2^i,
+* T(): the paper's notation table defines it as a job's duration according to a cost model and does
+  not print that model.  Here the caller supplies it in the form the packed execution has: for degree d = 2^i,
   T(H, d) = t_base[i] + sum_k H_k t_config[i][k]  (the base model's share grows with the packed
   tokens, every adapter adds its own low-rank work).
-* Alg. 1 returns "argmin T(p)" over the candidates; a candidate is a set of concurrent jobs, not a
+* Alg. 1 returns the candidate p with the least T(p); a candidate is a set of concurrent jobs, not a
   whole schedule, so the only duration it has is that of the remaining rank-work at its rate.  The
   text says DTM maximises the instantaneous throughput (the section's first expression); both say
   the same: the candidate with the largest  sum_j F_j  is returned (first one wins a tie).
@@ -28,7 +28,7 @@ Readings where the paper leaves a choice:
   bytes; read as c_grad x M_param (c_grad gradient-sized buffers: gradient, momentum, velocity).
   The sharded forms name M_grad and M_opt separately: M_grad = M_param (the gradient proper),
   M_opt = (c_grad - 1) M_param, which adds up to the unsharded total.
-* Appendix B, activation memory b x s x r x c_prec is "for each block": counted once per layer and
+* Appendix B gives the activation memory b x s x r x c_prec per block: counted once per layer and
   per projection that carries an adapter.
 """
 from __future__ import annotations
