@@ -51,6 +51,11 @@ CASES = {
     # long segments: the fused dA pass splits its token walk and sums partial tiles
     "long": dict(dtype="bf16", D=512, Ks=(128, 64), lengths=(4096, 4000), seg_adapter=(0, 1),
                  ranks=((64, 32), (64, 96)), scales=((1.0, 2.0), (0.5, 1.0))),
+    # more adapters than one kernel argument carries: the description takes the chunked upload path in every projection
+    "many_adapters": dict(dtype="bf16", D=136, Ks=(72, 200), lengths=tuple(3 + (7 * i) % 41 for i in range(140)),
+                          seg_adapter=tuple((11 * i) % 100 for i in range(140)),
+                          ranks=(tuple(1 + (5 * k) % 40 for k in range(100)), tuple(8 + (3 * k) % 50 for k in range(100))),
+                          scales=((1.0,) * 100, (0.5,) * 100)),
     "f32": dict(dtype="f32", D=64, Ks=(48, 32), lengths=(40, 50), seg_adapter=(0, 1),
                 ranks=((4, 8), (8, 2)), scales=((4.0, 2.0), (2.0, 8.0))),
     "single": dict(dtype="bf16", D=64, Ks=(64,), lengths=(40,), seg_adapter=(0,), ranks=((8,),), scales=((2.0,),)),
