@@ -35,6 +35,8 @@ def build_and_run(san_compile, san_link, args, env_extra):
         env = dict(os.environ, **env_extra)
         env.pop("LD_PRELOAD", None)
         run = subprocess.run([exe, *args], capture_output=True, text=True, env=env, timeout=900)
+        if run.returncode != 0 and "unexpected memory mapping" in run.stderr:
+            pytest.skip("the sanitizer runtime cannot map its shadow memory on this kernel (address-space layout), nothing ran")
         assert run.returncode == 0, (run.stdout[-2000:], run.stderr[-4000:])
         assert run.stdout.strip().startswith("ok "), run.stdout
         assert "Sanitizer" not in run.stderr and "runtime error" not in run.stderr, run.stderr[-4000:]
