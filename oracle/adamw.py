@@ -33,12 +33,18 @@ class Hyper:
     eps: float = 1e-8
     weight_decay: float = 0.0
     step: int = 1
+    grad_scale: float = 1.0   # the adapter's own multiplier on its gradient (see step_tensor)
 
 
 def step_tensor(theta, g, m, v, hp: Hyper) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """One AdamW update of one tensor: returns (theta, m, v) after the step, all fp64."""
+    """One AdamW update of one tensor: returns (theta, m, v) after the step, all fp64.
+
+    Every adapter of a packed run has its own data and its own loss (section 2.4), so what turns the
+    gradient the backward pass wrote into the gradient of that adapter's objective - the normalisation
+    by its own batch size (a per-job knob, Table 1), a clipping coefficient from its own gradient norm -
+    is a factor per adapter: g <- grad_scale * g before the rule is applied."""
     theta = np.asarray(theta, dtype=np.float64)
-    g = np.asarray(g, dtype=np.float64)
+    g = float(hp.grad_scale) * np.asarray(g, dtype=np.float64)
     m = np.asarray(m, dtype=np.float64)
     v = np.asarray(v, dtype=np.float64)
     lr, b1, b2 = float(hp.lr), float(hp.beta1), float(hp.beta2)

@@ -102,3 +102,25 @@ def test_each_adapter_uses_its_own_hyperparameters():
         b, mb, vb = oracle.adamw.step_tensor(B[k], dB[k], 0 * B[k], 0 * B[k], hp[k])
         assert np.array_equal(A2[k], a) and np.array_equal(B2[k], b) and np.array_equal(mA[k], ma) and np.array_equal(vB[k], vb)
     assert not np.allclose(A2[0] - A[0], (A2[1] - A[1])[:, :2])
+
+
+def test_gradient_multiplier():
+    """The adapter's own factor on its gradient: the hand-worked step with g = 2 and factor 1/4; equality, bit for bit,
+    with the unscaled rule on the scaled gradient; the regime where the update is linear in the factor (eps far above
+    the gradient: theta' = -lr s g / (|s g| + eps)); factor 0 leaves only the decay."""
+    g = json.load(open(os.path.join(GOLDEN, "adamw_hand_worked.json")))
+    sc = g["scaled"]
+    th, m, v = oracle.adamw.step_tensor([g["theta0"]], [sc["grad"]], [0.0], [0.0],
+                                        Hyper(g["lr"], g["beta1"], g["beta2"], g["eps"], 0.0, 1, sc["grad_scale"]))
+    assert th[0] == pytest.approx(sc["theta"], rel=1e-15) and m[0] == sc["m"] and v[0] == sc["v"]
+    rng = np.random.default_rng(31)
+    th0, gr, m0, v0 = rng.standard_normal(40), rng.standard_normal(40), rng.standard_normal(40), rng.random(40)
+    for s_ in (0.5, 3.0, -0.125):
+        a = oracle.adamw.step_tensor(th0, gr, m0, v0, Hyper(1e-2, 0.9, 0.99, 1e-8, 0.1, 3, s_))
+        b = oracle.adamw.step_tensor(th0, s_ * gr, m0, v0, Hyper(1e-2, 0.9, 0.99, 1e-8, 0.1, 3, 1.0))
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+    th, _, _ = oracle.adamw.step_tensor([0.0], [2.0], [0.0], [0.0], Hyper(1.0, 0.5, 0.5, 1000.0, 0.0, 1, 0.25))
+    assert th[0] == pytest.approx(-0.5 / 1000.5, rel=1e-14)
+    th, m, v = oracle.adamw.step_tensor([2.0], [7.0], [0.0], [0.0], Hyper(0.1, 0.9, 0.99, 1e-8, 0.5, 1, 0.0))
+    assert th[0] == pytest.approx(2.0 * 0.95) and m[0] == 0.0 and v[0] == 0.0
