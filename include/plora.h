@@ -254,6 +254,7 @@ plora_status plora_linear_bwd_nf4(const plora_desc *desc, const void *x, const v
  * parameters and optimizer state; appendix B: AdamW with gradient, momentum and velocity per
  * adapter; Table 1: the learning rate is a per-job hyperparameter).  AdamW as published, in the
  * order the common frameworks apply it, for every element of A_k and B_k of every adapter k:
+ *     g <- grad_scale_k g
  *     theta <- theta (1 - lr_k wd_k);  m <- beta1_k m + (1 - beta1_k) g;  v <- beta2_k v + (1 - beta2_k) g^2
  *     theta <- theta - lr_k (m / (1 - beta1_k^t_k)) / (sqrt(v / (1 - beta2_k^t_k)) + eps_k)
  * fp32 arithmetic.  The parameter proper is the fp32 master copy; the copy in the layer's I/O type
@@ -262,6 +263,10 @@ plora_status plora_linear_bwd_nf4(const plora_desc *desc, const void *x, const v
 typedef struct {
     float lr, beta1, beta2, eps, weight_decay;
     int32_t step;                 /* t of this update: 1 for the adapter's first step                */
+    float grad_scale;             /* multiplier on the adapter's gradient before the rule, g <- grad_scale g:
+                                     every adapter has its own data and loss (section 2.4), so the factor
+                                     that normalises by its own batch size (a per-job knob, Table 1) or
+                                     clips by its own gradient norm is per adapter.  1 for none; finite   */
 } plora_adamw_hparams;
 
 /* One side (all A_k, or all B_k): HOST arrays of n_adapters DEVICE pointers, 16-byte aligned,
@@ -280,7 +285,8 @@ typedef struct {
  * workspace).  Only T-independent parts of desc are used: d_in, d_out, n_adapters, rank, dtype
  * (the description is validated as a whole).  hp: HOST array of n_adapters.  Errors as for the
  * other calls: PLORA_ERR_NULL for a missing table or pointer (param and master both absent, master
- * absent with bf16), PLORA_ERR_ALIGN, PLORA_ERR_SHAPE for step < 1 or betas outside [0, 1).
+ * absent with bf16), PLORA_ERR_ALIGN, PLORA_ERR_SHAPE for step < 1, betas outside [0, 1) or a
+ * grad_scale that is not finite.
  */
 plora_status plora_adamw_step(const plora_desc *desc, const plora_adamw_side *A, const plora_adamw_side *B,
                               const plora_adamw_hparams *hp, void *hip_stream);

@@ -4,6 +4,7 @@
 // state and learning rate (section 2.4; appendix B counts gradient, momentum and velocity per
 // adapter for AdamW; Table 1 lists the learning rate among the per-job knobs).  The rule is the
 // published AdamW, in the order the common frameworks apply it:
+//     g <- grad_scale g  (the adapter's own factor: its loss normalisation or clipping coefficient)
 //     theta <- theta (1 - lr wd);  m <- b1 m + (1 - b1) g;  v <- b2 v + (1 - b2) g^2;
 //     theta <- theta - lr (m / (1 - b1^t)) / (sqrt(v / (1 - b2^t)) + eps)
 // One launch updates up to kAdamwTensors tensors of different sizes and hyperparameters ("multi-
@@ -25,7 +26,7 @@ struct AdamwJob {
     float *m, *v;
     uint32_t numel, chunk0; // chunk0 = index of this tensor's first workgroup in the launch
     float lr, beta1, beta2, eps, decay, c1, c2;   // decay = 1 - lr wd; c1 = 1 / (1 - beta1^t); c2 = 1 / (1 - beta2^t)
-    uint32_t pad;
+    float gscale;           // multiplier on the gradient
 };
 struct AdamwBatch {
     int32_t n, pad;
@@ -43,6 +44,7 @@ __device__ inline uint32_t adamw_pack_bf16x2(float lo, float hi)
 
 __device__ inline float adamw_one(float &th, float g, float &m, float &v, const AdamwJob &j)
 {
+    g = j.gscale * g;
     th = th * j.decay;
     m = j.beta1 * m + (1.0f - j.beta1) * g;
     v = j.beta2 * v + (1.0f - j.beta2) * g * g;
@@ -120,7 +122,7 @@ hipError_t launch_adamw(const AdamwTensor *t, int n, bool bf16, hipStream_t st)
             for (int s = 0; s < t[i].step && (p1 > 0.0 || p2 > 0.0); ++s) { p1 *= (double)t[i].beta1; p2 *= (double)t[i].beta2; }
             j.c1 = (float)(1.0 / (1.0 - p1));
             j.c2 = (float)(1.0 / (1.0 - p2));
-            j.pad = 0;
+            j.gscale = t[i].grad_scale;
         }
         if (chunks == 0) continue;
         if (bf16) hipLaunchKernelGGL(k_adamw<true>, dim3(chunks), dim3(256), 0, st, b);

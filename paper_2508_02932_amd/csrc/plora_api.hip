@@ -5,6 +5,7 @@
 #include "plora_bench.h"
 #include "plora_debug.h"
 
+#include <cmath>
 #include <cstring>
 #include <algorithm>
 #include <memory>
@@ -836,7 +837,7 @@ static plora_status adamw_collect(const plora_desc *d, const plora_adamw_side *s
             return PLORA_ERR_ALIGN;
         t.numel = (uint64_t)d->rank[k] * (uint64_t)(is_A ? d->d_in : d->d_out);
         t.lr = hp[k].lr; t.beta1 = hp[k].beta1; t.beta2 = hp[k].beta2; t.eps = hp[k].eps;
-        t.weight_decay = hp[k].weight_decay; t.step = hp[k].step;
+        t.weight_decay = hp[k].weight_decay; t.step = hp[k].step; t.grad_scale = hp[k].grad_scale;
         out.push_back(t);
     }
     return PLORA_OK;
@@ -851,7 +852,8 @@ plora_status plora_adamw_step(const plora_desc *desc, const plora_adamw_side *A,
         if (desc->n_adapters == 0) return PLORA_OK;
         if (!hp) return PLORA_ERR_NULL;
         for (int32_t k = 0; k < desc->n_adapters; ++k)
-            if (hp[k].step < 1 || !(hp[k].beta1 >= 0.f && hp[k].beta1 < 1.f) || !(hp[k].beta2 >= 0.f && hp[k].beta2 < 1.f))
+            if (hp[k].step < 1 || !(hp[k].beta1 >= 0.f && hp[k].beta1 < 1.f) || !(hp[k].beta2 >= 0.f && hp[k].beta2 < 1.f) ||
+                !std::isfinite(hp[k].grad_scale))
                 return PLORA_ERR_SHAPE;
         std::vector<AdamwTensor> jobs;
         jobs.reserve(2 * (size_t)desc->n_adapters);

@@ -522,6 +522,7 @@ struct AdamwTensor {
     uint64_t numel;
     float lr, beta1, beta2, eps, weight_decay;
     int32_t step;
+    float grad_scale;
 };
 // AdamW step of n tensors (any sizes, each with its own hyperparameters); bf16 tells the type of `param`.
 hipError_t launch_adamw(const AdamwTensor *t, int n, bool bf16, hipStream_t st);

@@ -81,7 +81,7 @@ class plora_plan_summary(C.Structure):
 
 class plora_adamw_hparams(C.Structure):
     _fields_ = [("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float), ("eps", C.c_float),
-                ("weight_decay", C.c_float), ("step", C.c_int32)]
+                ("weight_decay", C.c_float), ("step", C.c_int32), ("grad_scale", C.c_float)]
 
 
 class plora_adamw_side(C.Structure):
@@ -509,7 +509,7 @@ def plora_linear_bwd_nf4(d: Desc, x, W_codes, W_absmax, A: Sequence, B: Sequence
 def plora_adamw_step(d: Desc, A_side: dict, B_side: dict, hparams: Sequence, stream=None) -> None:
     """Enqueues the per-adapter AdamW step.  A_side / B_side: dicts with the keys param, master, grad, m, v, each a
     list of n_adapters device tensors (param or master may be None); hparams: one (lr, beta1, beta2, eps,
-    weight_decay, step) tuple per adapter."""
+    weight_decay, step[, grad_scale]) tuple per adapter (grad_scale: the adapter's multiplier on its gradient, 1 if left out)."""
     keep = []
 
     def side(s):
@@ -521,7 +521,7 @@ def plora_adamw_step(d: Desc, A_side: dict, B_side: dict, hparams: Sequence, str
         return plora_adamw_side(*tabs)
 
     sa, sb = side(A_side), side(B_side)
-    hp = (plora_adamw_hparams * max(len(hparams), 1))(*[plora_adamw_hparams(*h) for h in hparams])
+    hp = (plora_adamw_hparams * max(len(hparams), 1))(*[plora_adamw_hparams(*(tuple(h) + (1.0,))[:7]) for h in hparams])
     _check(lib().plora_adamw_step(d.ref, C.byref(sa), C.byref(sb), hp, _stream(stream)))
 
 

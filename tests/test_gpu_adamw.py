@@ -50,11 +50,12 @@ def run_steps(dtype, D, K, ranks, hps, n_steps, with_master=True, seed=0):
     for step in range(n_steps):
         print(f"[case] adamw {dtype} step {step + 1} ranks={ranks} master={with_master}", flush=True)
         grads = {s: [(rng.standard_normal(sh) * 0.05).astype(np.float32) for sh in shapes[s]] for s in "AB"}
-        hp_now = [Hyper(f32(h.lr), f32(h.beta1), f32(h.beta2), f32(h.eps), f32(h.weight_decay), h.step + step) for h in hps]
+        hp_now = [Hyper(f32(h.lr), f32(h.beta1), f32(h.beta2), f32(h.eps), f32(h.weight_decay), h.step + step, f32(h.grad_scale))
+                  for h in hps]
         for s in "AB":
             dev[s]["grad"] = [torch.from_numpy(gr).cuda() for gr in grads[s]]
         plora.plora_adamw_step(desc, dev["A"], dev["B"],
-                               [(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step) for h in hp_now])
+                               [(h.lr, h.beta1, h.beta2, h.eps, h.weight_decay, h.step, h.grad_scale) for h in hp_now])
         torch.cuda.synchronize()
         A2, B2, mA, vA, mB, vB = oracle.adamw.step_adapters(host["A"], host["B"], grads["A"], grads["B"], state["A"]["m"],
                                                             state["A"]["v"], state["B"]["m"], state["B"]["v"], hp_now)
@@ -77,7 +78,7 @@ def run_steps(dtype, D, K, ranks, hps, n_steps, with_master=True, seed=0):
         assert all(np.isfinite(v) and v <= TOL for v in errs.values()), {k: v for k, v in errs.items() if not v <= TOL}
 
 
-HP3 = [Hyper(2e-3, 0.9, 0.999, 1e-8, 0.0, 1), Hyper(4e-4, 0.8, 0.95, 1e-6, 0.1, 5), Hyper(2e-5, 0.9, 0.99, 1e-8, 0.01, 1)]
+HP3 = [Hyper(2e-3, 0.9, 0.999, 1e-8, 0.0, 1), Hyper(4e-4, 0.8, 0.95, 1e-6, 0.1, 5, 0.125), Hyper(2e-5, 0.9, 0.99, 1e-8, 0.01, 1, 3.0)]
 
 
 def test_adamw_bf16_three_adapters_three_steps():
@@ -91,7 +92,7 @@ def test_adamw_f32_in_place_and_with_master():
 
 def test_adamw_more_tensors_than_one_launch_carries():
     n = 25                                                               # 50 tensors: two launches
-    hps = [Hyper(1e-3 * (1 + k % 3), 0.9, 0.99, 1e-8, 0.02 * (k % 2), 1 + k % 4) for k in range(n)]
+    hps = [Hyper(1e-3 * (1 + k % 3), 0.9, 0.99, 1e-8, 0.02 * (k % 2), 1 + k % 4, (1.0, 0.5, 1.0 / 1024)[k % 3]) for k in range(n)]
     run_steps("bf16", 72, 56, [1 + (7 * k) % 24 for k in range(n)], hps, 2)
 
 
@@ -115,7 +116,8 @@ def test_adamw_rejects_bad_arguments():
                     "m": z(16, 4), "v": z(16, 4)}
     ok = (1e-3, 0.9, 0.99, 1e-8, 0.0, 1)
     plora.plora_adamw_step(d, side(), side(), [ok])
-    for bad, code in (((1e-3, 0.9, 0.99, 1e-8, 0.0, 0), 2), ((1e-3, 1.0, 0.99, 1e-8, 0.0, 1), 2)):
+    for bad, code in (((1e-3, 0.9, 0.99, 1e-8, 0.0, 0), 2), ((1e-3, 1.0, 0.99, 1e-8, 0.0, 1), 2),
+                      ((1e-3, 0.9, 0.99, 1e-8, 0.0, 1, float("inf")), 2)):
         with pytest.raises(plora.PloraError) as e:
             plora.plora_adamw_step(d, side(), side(), [bad])
         assert e.value.code == code
