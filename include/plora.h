@@ -68,8 +68,9 @@ typedef enum {
     PLORA_ERR_UNSUPPORTED = 8,  /* unknown dtype or weight layout                               */
     PLORA_ERR_HIP = 9,          /* a HIP call failed (launch error)                             */
     PLORA_ERR_INTERNAL = 10,    /* host memory allocation failed or another internal error      */
-    PLORA_ERR_GROUP = 11        /* grouped call: n_proj outside [1, PLORA_MAX_GROUP], or the
-                                   projections differ in dtype, T, d_in, segments or adapters    */
+    PLORA_ERR_GROUP = 11        /* grouped call: n_proj outside [1, PLORA_MAX_GROUP], the projections
+                                   differ in dtype, T, d_in, segments or adapters, or both dx and
+                                   dx_sum are given                                              */
 } plora_status;
 
 typedef enum { PLORA_BF16 = 0, PLORA_F32 = 1 } plora_dtype;
@@ -204,7 +205,12 @@ plora_status plora_lora_bwd(const plora_desc *desc, const void *x, const void *c
  *                 n_adapters (PLORA_ERR_GROUP otherwise)
  *   W, y, dy, dx, h_saved   HOST arrays of n_proj DEVICE pointers, entry p as in the plain call for projection p
  *                 (dx, h_saved: the array or single entries may be NULL; dx[p] is projection p's own dy_p W_p^T +
- *                 g_p A_p^T - summing them over p is the caller's)
+ *                 g_p A_p^T)
+ *   dx_sum        DEVICE [T][d_in] or NULL: the gradient of the shared input, sum over p of dy_p W_p^T + g_p A_p^T
+ *                 (case 4 of appendix C.2 for every projection that reads x).  Projection 0 overwrites it, every
+ *                 further projection's GEMM adds to it in its epilogue, so no projection's own dx is ever stored;
+ *                 in bf16 the running sum is rounded after every projection, as a chain of bf16 additions would.
+ *                 Give dx or dx_sum, not both (PLORA_ERR_GROUP)
  *   A, B, dA, dB  HOST arrays of n_proj HOST arrays of n_adapters DEVICE pointers; dA / dB: the array, or entry p of
  *                 both, may be NULL (no weight gradients for that projection)
  * The workspace must hold plora_group_workspace_bytes(group) bytes (0 for an invalid group).  PLORA_F32 groups are
@@ -220,8 +226,9 @@ plora_status plora_group_fwd(const plora_group *group, const void *x, const void
                              float *const *h_saved, void *workspace, size_t ws_bytes, void *hip_stream);
 plora_status plora_group_bwd(const plora_group *group, const void *x, const void *const *W,
                              const void *const *const *A, const void *const *const *B, const void *const *dy,
-                             const float *const *h_saved, void *const *dx, float *const *const *dA,
-                             float *const *const *dB, void *workspace, size_t ws_bytes, void *hip_stream);
+                             const float *const *h_saved, void *const *dx, void *dx_sum,
+                             float *const *const *dA, float *const *const *dB, void *workspace, size_t ws_bytes,
+                             void *hip_stream);
 
 /*
  * The layer on a base weight stored as 4-bit NormalFloat (NF4, the storage QLoRA publishes; the paper applies packed

@@ -63,7 +63,7 @@ hipError_t launch_f32_lowrank(const MetaView &mv, const MetaHeader &h, int mode,
 // 64x64 output tile per block, 4x4 outputs per thread, contraction staged through LDS 16 at a time.
 // WK: the contraction index is W's row index (forward with W [d_in][d_out], backward with W [d_out][d_in]).
 template <bool FWD, bool WK>
-__global__ void __launch_bounds__(256) k_f32_gemm(MetaView mv, const float *S, const float *W, const float *side, float *Cout)
+__global__ void __launch_bounds__(256) k_f32_gemm(MetaView mv, const float *S, const float *W, const float *side, float *Cout, int accumulate)
 {
     __shared__ float sA[16][64 + 1];   // [kk][row]
     __shared__ float sB[16][64 + 1];   // [kk][col]
@@ -124,6 +124,7 @@ __global__ void __launch_bounds__(256) k_f32_gemm(MetaView mv, const float *S, c
                 }
                 v += l;
             }
+            if (accumulate) v += (double)Cout[t * N + n];
             Cout[t * N + n] = (float)v;
         }
     }
@@ -165,16 +166,17 @@ hipError_t launch_f32_expand(const MetaView &mv, const MetaHeader &h, bool to_y,
 }
 
 hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward, const float *S, const float *W,
-                           const float *side, float *C, hipStream_t st)
+                           const float *side, float *C, bool accumulate, hipStream_t st)
 {
     if (h.T == 0) return hipSuccess;
+    const int acc = accumulate ? 1 : 0;
     const int64_t N = forward ? h.K : h.D;
     dim3 grid((unsigned)((N + 63) / 64), (unsigned)((h.T + 63) / 64));
     const bool wk = forward != (h.w_out_in != 0);
-    if (forward && wk) hipLaunchKernelGGL((k_f32_gemm<true, true>), grid, dim3(256), 0, st, mv, S, W, side, C);
-    else if (forward) hipLaunchKernelGGL((k_f32_gemm<true, false>), grid, dim3(256), 0, st, mv, S, W, side, C);
-    else if (wk) hipLaunchKernelGGL((k_f32_gemm<false, true>), grid, dim3(256), 0, st, mv, S, W, side, C);
-    else hipLaunchKernelGGL((k_f32_gemm<false, false>), grid, dim3(256), 0, st, mv, S, W, side, C);
+    if (forward && wk) hipLaunchKernelGGL((k_f32_gemm<true, true>), grid, dim3(256), 0, st, mv, S, W, side, C, acc);
+    else if (forward) hipLaunchKernelGGL((k_f32_gemm<true, false>), grid, dim3(256), 0, st, mv, S, W, side, C, acc);
+    else if (wk) hipLaunchKernelGGL((k_f32_gemm<false, true>), grid, dim3(256), 0, st, mv, S, W, side, C, acc);
+    else hipLaunchKernelGGL((k_f32_gemm<false, false>), grid, dim3(256), 0, st, mv, S, W, side, C, acc);
     return hipGetLastError();
 }
 

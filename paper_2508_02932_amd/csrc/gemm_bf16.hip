@@ -103,7 +103,16 @@ __device__ inline void wait_vmcnt_048(int n)
     else wait_vmcnt<0>();
 }
 
-template <bool FWD>
+// 8 bf16 + 8 bf16 in fp32, rounded to nearest even (the accumulating epilogue)
+__device__ inline uint32_t add_bf16x2(uint32_t a, uint32_t b)
+{
+    return pack_bf16x2(__uint_as_float(a << 16) + __uint_as_float(b << 16),
+                       __uint_as_float(a & 0xffff0000u) + __uint_as_float(b & 0xffff0000u));
+}
+
+// ACC: the result is added to what Cout holds (read in the epilogue, one more rounding to bf16), for gradients of an
+// input that several projections share.
+template <bool FWD, bool ACC = false>
 __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles, const int32_t *__restrict__ order,
                                               const SegInfo *__restrict__ segs,
                                               const AdapterInfo *__restrict__ ads, const uint16_t *__restrict__ S,
@@ -540,7 +549,17 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
                 const int row = (lane >> 3) + 8 * j, c = lane & 7;
                 const uint4 v = *reinterpret_cast<const uint4 *>(stg + row * 128 + ((c ^ (row & 7)) * 16));
                 const int m = em0 + wm0 + mi * 32 + row, n = en0 + wn0 + c * 8;
-                if (m < M && n < N) *reinterpret_cast<uint4 *>(Cout + (int64_t)m * N + n) = v;
+                if (m < M && n < N) {
+                    if constexpr (ACC) {
+                        const uint4 old = *reinterpret_cast<const uint4 *>(Cout + (int64_t)m * N + n);
+                        uint4 sum;
+                        sum.x = add_bf16x2(old.x, v.x); sum.y = add_bf16x2(old.y, v.y);
+                        sum.z = add_bf16x2(old.z, v.z); sum.w = add_bf16x2(old.w, v.w);
+                        *reinterpret_cast<uint4 *>(Cout + (int64_t)m * N + n) = sum;
+                    } else {
+                        *reinterpret_cast<uint4 *>(Cout + (int64_t)m * N + n) = v;
+                    }
+                }
             }
         }
     }
@@ -549,14 +568,14 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
     wait_vmcnt<0>();                          // no direct-to-LDS load may outlive the workgroup
 }
 
-template <bool FWD>
+template <bool FWD, bool ACC>
 static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, int64_t Kd, int64_t N, const void *S, const void *W,
                                  const void *side, const void *ap, const void *zero, void *C, hipStream_t st)
 {
     const int tiles_m = (int)((h.T + BM - 1) / BM), tiles_n = (int)((N + BN - 1) / BN);
-    auto kern = k_gemm<FWD>;
+    auto kern = k_gemm<FWD, ACC>;
     {
-        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(kern), FWD ? 5 : 6);
+        hipError_t e = allow_full_lds(reinterpret_cast<const void *>(kern), (FWD ? 5 : 6) + (ACC ? 4 : 0));
         if (e != hipSuccess) return e;
     }
     // persistent grid: one workgroup per compute unit (256 on an MI355X; a workgroup takes a whole CU's LDS)
@@ -575,11 +594,15 @@ static hipError_t launch_variant(const MetaView &mv, const MetaHeader &h, int64_
 
 hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool w_rows_contract, int64_t Kd, int64_t N,
                             const void *S, const void *W, const void *side, const void *ap, const void *zero, void *C,
-                            hipStream_t st)
+                            bool accumulate, hipStream_t st)
 {
     if (h.T == 0) return hipSuccess;
-    if (w_rows_contract) return launch_variant<true>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
-    return launch_variant<false>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
+    if (accumulate) {
+        if (w_rows_contract) return launch_variant<true, true>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
+        return launch_variant<false, true>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
+    }
+    if (w_rows_contract) return launch_variant<true, false>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
+    return launch_variant<false, false>(mv, h, Kd, N, S, W, side, ap, zero, C, st);
 }
 
 }  // namespace plora

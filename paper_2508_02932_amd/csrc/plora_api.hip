@@ -320,7 +320,7 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
             return PLORA_OK;
         }
         { Bracket b(0, st);
-          PL_TRY(launch_f32_gemm(mv, m.hdr, true, xf, static_cast<const float *>(W), hf, static_cast<float *>(y), st)); }
+          PL_TRY(launch_f32_gemm(mv, m.hdr, true, xf, static_cast<const float *>(W), hf, static_cast<float *>(y), false, st)); }
         return PLORA_OK;
     }
 
@@ -338,14 +338,14 @@ static plora_status forward_impl(const plora_desc *desc, const void *x, const vo
         return PLORA_OK;
     }
     { Bracket b(0, st);
-      PL_TRY(launch_gemm_bf16(mv, m.hdr, !w_out_in, desc->d_in, desc->d_out, x, W, hb, ws + L.ap, ws + L.zero, y, st)); }
+      PL_TRY(launch_gemm_bf16(mv, m.hdr, !w_out_in, desc->d_in, desc->d_out, x, W, hb, ws + L.ap, ws + L.zero, y, false, st)); }
     return PLORA_OK;
 }
 
 static plora_status backward_impl(const plora_desc *desc, const void *x, const void *W, const void *const *A,
                                   const void *const *B, const void *dy, const float *h_saved, void *dx, float *const *dA,
                                   float *const *dB, void *workspace, size_t ws_bytes, void *hip_stream, bool lora_only = false,
-                                  bool check_only = false, unsigned steps = kStepsAll)
+                                  bool check_only = false, unsigned steps = kStepsAll, bool dx_accumulate = false)
 {
     const bool want_w = (dA != nullptr) || (dB != nullptr);
     if (desc && want_w && desc->n_adapters > 0 && (!dA || !dB)) {
@@ -405,7 +405,7 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
             PL_TRY(launch_f32_expand(mv, m.hdr, false, static_cast<float *>(dx), gf, st));
         } else if (dx && desc->T > 0) {
             Bracket b(1, st);
-            PL_TRY(launch_f32_gemm(mv, m.hdr, false, dyf, static_cast<const float *>(W), gf, static_cast<float *>(dx), st));
+            PL_TRY(launch_f32_gemm(mv, m.hdr, false, dyf, static_cast<const float *>(W), gf, static_cast<float *>(dx), dx_accumulate, st));
         }
         return PLORA_OK;
     }
@@ -435,7 +435,7 @@ static plora_status backward_impl(const plora_desc *desc, const void *x, const v
         PL_TRY(launch_expand_bf16(mv, m.hdr, dx, desc->d_in, gb, ap, m.hdr.w_out_in ? desc->d_out : desc->d_in, ws + L.zero, st));
     } else if (dx && desc->T > 0) {
         Bracket b(1, st);
-        PL_TRY(launch_gemm_bf16(mv, m.hdr, m.hdr.w_out_in != 0, desc->d_out, desc->d_in, dy, W, gb, ap, ws + L.zero, dx, st));
+        PL_TRY(launch_gemm_bf16(mv, m.hdr, m.hdr.w_out_in != 0, desc->d_out, desc->d_in, dy, W, gb, ap, ws + L.zero, dx, dx_accumulate, st));
     }
     return PLORA_OK;
 }
@@ -584,20 +584,22 @@ static plora_status group_forward(const plora_group *g, const void *x, const voi
 
 static plora_status group_backward(const plora_group *g, const void *x, const void *const *W, const void *const *const *A,
                                    const void *const *const *B, const void *const *dy, const float *const *h_saved,
-                                   void *const *dx, float *const *const *dA, float *const *const *dB, void *workspace,
-                                   size_t ws_bytes, void *hip_stream)
+                                   void *const *dx, void *dx_sum, float *const *const *dA, float *const *const *dB,
+                                   void *workspace, size_t ws_bytes, void *hip_stream)
 {
     GroupPlan gp;
     plora_status ps = plan_group(g, gp);
     if (ps != PLORA_OK) return ps;
     if (!W || !dy || (g->desc[0].n_adapters > 0 && (!A || !B))) return PLORA_ERR_NULL;
+    if (dx && dx_sum) return PLORA_ERR_GROUP;            // one or the other
     if (!workspace || ws_bytes < gp.total) return PLORA_ERR_WORKSPACE;
     if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PLORA_ERR_ALIGN;
     char *ws = static_cast<char *>(workspace);
+    // dx_sum: every projection's dX GEMM targets the one tensor, the first overwriting it, the others adding to it
     auto run = [&](int p, bool check, unsigned steps) {
         return backward_impl(&g->desc[p], x, W[p], A ? A[p] : nullptr, B ? B[p] : nullptr, dy[p], h_saved ? h_saved[p] : nullptr,
-                             dx ? dx[p] : nullptr, dA ? dA[p] : nullptr, dB ? dB[p] : nullptr, ws + gp.ws_off[p],
-                             gp.m[p]->ws.total, hip_stream, false, check, steps);
+                             dx_sum ? dx_sum : (dx ? dx[p] : nullptr), dA ? dA[p] : nullptr, dB ? dB[p] : nullptr, ws + gp.ws_off[p],
+                             gp.m[p]->ws.total, hip_stream, false, check, steps, dx_sum != nullptr && p > 0);
     };
     for (int p = 0; p < gp.n; ++p)
         if ((ps = run(p, true, kStepsAll)) != PLORA_OK) return ps;
@@ -1006,11 +1008,11 @@ plora_status plora_group_fwd(const plora_group *group, const void *x, const void
 
 plora_status plora_group_bwd(const plora_group *group, const void *x, const void *const *W, const void *const *const *A,
                              const void *const *const *B, const void *const *dy, const float *const *h_saved,
-                             void *const *dx, float *const *const *dA, float *const *const *dB, void *workspace,
-                             size_t ws_bytes, void *hip_stream)
+                             void *const *dx, void *dx_sum, float *const *const *dA, float *const *const *dB,
+                             void *workspace, size_t ws_bytes, void *hip_stream)
 {
     PL_GUARDED(PLORA_ERR_INTERNAL,
-        return group_backward(group, x, W, A, B, dy, h_saved, dx, dA, dB, workspace, ws_bytes, hip_stream);
+        return group_backward(group, x, W, A, B, dy, h_saved, dx, dx_sum, dA, dB, workspace, ws_bytes, hip_stream);
     )
 }
 

@@ -479,9 +479,10 @@ hipError_t launch_skinny_bf16(const MetaView &mv, const MetaHeader &h, int mode,
 //   otherwise       : Wop = W [N][Kd] (contraction index is contiguous),     ext_k = ap + GemmSeg::ap_off [N][rp]
 //   W[d_in][d_out]: forward (S = x, Kd = d_in, N = d_out) is the first form, backward (S = dy, Kd = d_out, N = d_in)
 //   the second; W[d_out][d_in]: the other way round.
+//   accumulate: C += the product (C is read in the epilogue and the sum rounded once more), otherwise C is overwritten
 hipError_t launch_gemm_bf16(const MetaView &mv, const MetaHeader &h, bool w_rows_contract, int64_t Kd, int64_t N,
                             const void *S, const void *W, const void *side, const void *ap, const void *zero, void *C,
-                            hipStream_t st);
+                            bool accumulate, hipStream_t st);
 // Stand-alone low-rank update C[T][N] += side * op_k (bf16, one rounding): side = bf16 low-rank factor [len][rp] per
 // segment, opT = padded small matrices [N][rp] (adapter k at N * (ap_off_k / table_rows)).
 hipError_t launch_expand_bf16(const MetaView &mv, const MetaHeader &h, void *C, int64_t N, const void *side, const void *opT,
@@ -507,7 +508,7 @@ int skinny_splits(const MetaHeader &h, int64_t C);
 hipError_t launch_f32_lowrank(const MetaView &mv, const MetaHeader &h, int mode, const float *S, int64_t C,
                               float *out, hipStream_t st);
 hipError_t launch_f32_gemm(const MetaView &mv, const MetaHeader &h, bool forward, const float *S, const float *W,
-                           const float *side, float *C, hipStream_t st);   // W's layout: h.w_out_in
+                           const float *side, float *C, bool accumulate, hipStream_t st);   // W's layout: h.w_out_in
 // to_y: y += scale_k h B_k (side = h);  else dx += g A_k^T (side = g, which carries scale_k).
 hipError_t launch_f32_expand(const MetaView &mv, const MetaHeader &h, bool to_y, float *C, const float *side, hipStream_t st);
 hipError_t launch_f32_wgrad(const MetaView &mv, const MetaHeader &h, bool want_dA, const float *S, int64_t C,

@@ -159,7 +159,7 @@ def lib():
         L.plora_group_fwd.restype = C.c_int
         L.plora_group_fwd.argtypes = [C.POINTER(plora_group)] + [C.c_void_p] * 7 + [C.c_size_t, C.c_void_p]
         L.plora_group_bwd.restype = C.c_int
-        L.plora_group_bwd.argtypes = [C.POINTER(plora_group)] + [C.c_void_p] * 10 + [C.c_size_t, C.c_void_p]
+        L.plora_group_bwd.argtypes = [C.POINTER(plora_group)] + [C.c_void_p] * 11 + [C.c_size_t, C.c_void_p]
         L.plora_plan_lora_bytes.restype = C.c_double
         L.plora_plan_lora_bytes.argtypes = [C.POINTER(plora_plan_model), C.POINTER(plora_plan_lora), C.POINTER(plora_plan_sharding)]
         L.plora_plan_pack.restype = C.c_int
@@ -396,8 +396,9 @@ def plora_group_fwd(g: Group, x, W: Sequence, A: Sequence[Sequence], B: Sequence
 
 def plora_group_bwd(g: Group, x, W: Sequence, A: Sequence[Sequence], B: Sequence[Sequence], dy: Sequence,
                     h_saved: Optional[Sequence], dx: Optional[Sequence], dA: Optional[Sequence], dB: Optional[Sequence],
-                    workspace, stream=None) -> None:
-    """Enqueues the backward of every projection of the group (dx[p] is projection p's own input gradient)."""
+                    workspace, stream=None, dx_sum=None) -> None:
+    """Enqueues the backward of every projection of the group.  dx[p] is projection p's own input gradient; dx_sum
+    (instead of dx) receives their sum, the gradient of the shared input."""
     kw, pw = _ptr_array(W)
     ka, pa = _table_array(A)
     kb, pb = _table_array(B)
@@ -406,7 +407,7 @@ def plora_group_bwd(g: Group, x, W: Sequence, A: Sequence[Sequence], B: Sequence
     kdx, pdx = _ptr_array(dx)
     kda, pda = _table_array(dA)
     kdb, pdb = _table_array(dB)
-    _check(lib().plora_group_bwd(g.ref, _ptr(x), pw, pa, pb, pdy, ph, pdx, pda, pdb, _ptr(workspace),
+    _check(lib().plora_group_bwd(g.ref, _ptr(x), pw, pa, pb, pdy, ph, pdx, _ptr(dx_sum), pda, pdb, _ptr(workspace),
                                  workspace.numel() * workspace.element_size(), _stream(stream)))
 
 

@@ -207,3 +207,43 @@ def test_config4_groups_full_size(members):
         assert torch.equal(ref.h[:nh], dp.h[:nh]) and torch.equal(ref.y, dp.y) and torch.equal(ref.dx, dp.dx), lin.name
         del ref
         torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("case", ["qkv_one_pass", "cut_in_two", "four", "gate_up", "f32", "single"])
+def test_group_input_gradient_summed_in_the_epilogue(case):
+    """dx_sum: the gradient of the shared input, sum over the projections of dy_p W_p^T + g_p A_p^T, against the oracle's
+    per-projection dx added up in fp64; in bf16 also bit for bit against the chain of bf16 additions of the per-projection
+    results (what the accumulating epilogue is specified to equal).  The per-projection dx buffers stay untouched."""
+    import torch
+    import gpu_harness as gh
+    from paper_2508_02932_amd import plora
+    c = CASES[case]
+    n = len(c["Ks"])
+    print(f"[case] group dx_sum {case}", flush=True)
+    sys.stdout.flush()
+    layouts = [p % 2 for p in range(n)]
+    lins, tens, dps = run_group(case, layouts, [True] * n, [True] * n, [True] * n)      # per-projection dx for the chain
+    group = plora.Group([dp.desc for dp in dps])
+    guards: list = []
+    ws = gh.guarded((plora.plora_group_workspace_bytes(group),), torch.uint8, None, guards, "group workspace")
+    dx_sum = gh.guarded(tuple(dps[0].dx.shape), dps[0].dx.dtype, float("nan"), guards, "dx_sum")
+    chain = dps[0].dx.clone()
+    for dp in dps[1:]:
+        chain = chain + dp.dx
+    for dp in dps:
+        dp.dx.fill_(float("nan"))
+    lists = lambda name: [getattr(dp, name) for dp in dps]
+    plora.plora_group_bwd(group, dps[0].x, lists("W"), lists("A"), lists("B"), lists("dy"), lists("h"), None, lists("dA"), lists("dB"),
+                          ws, dx_sum=dx_sum)
+    torch.cuda.synchronize()
+    for name, base, nbytes in guards:
+        assert bool((base[:gh.GUARD_BYTES] == gh.GUARD_BYTE).all()) and bool((base[gh.GUARD_BYTES + nbytes:] == gh.GUARD_BYTE).all()), name
+    want = np.zeros(dps[0].dx.shape, dtype=np.float64)
+    for lin, t, dp in zip(lins, tens, dps):
+        gh.check_guards(dp)
+        assert bool(dp.dx.float().isnan().all()), "a per-projection dx was written"
+        want += oracle.loops.backward(make_problem(oracle, lin, t), t.dy)[0]
+    err = scaled_err(gh.to_np(dx_sum), want)
+    assert np.isfinite(err) and err <= TOL[c["dtype"]], (case, err)
+    if c["dtype"] == "bf16":
+        assert torch.equal(dx_sum, chain), "dx_sum is not the chain of bf16 additions of the per-projection results"

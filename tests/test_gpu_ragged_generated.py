@@ -129,6 +129,8 @@ def ragged_group(draw):
         lins.append(wl.small(f"ggen_{seed}_p{p}", "bf16", D, K, lengths, seg_adapter, ranks, scales, seed=7 * seed + p))
         opts.append((draw(st.sampled_from([0, 1])), draw(st.booleans()), draw(st.sampled_from([True, True, True, False])),
                      draw(st.sampled_from([True, True, False]))))
+    if draw(st.sampled_from([False, False, True])):      # one time in three: the summed input gradient instead of one dx each
+        opts = [o[:3] + ("sum",) for o in opts]
     return lins, opts
 
 
@@ -156,20 +158,26 @@ def test_generated_ragged_groups(case):
     ws = gh.guarded((plora.plora_group_workspace_bytes(group),), torch.uint8, None, guards, "group workspace")
     pick = lambda items, flags: [it if f else None for it, f in zip(items, flags)] if any(flags) else None
     save_h, want_w, want_dx = ([o[i] for o in opts] for i in (1, 2, 3))
+    use_sum = want_dx[0] == "sum"
+    dx_sum = gh.guarded(tuple(dps[0].dx.shape), torch.bfloat16, float("nan"), guards, "dx_sum") if use_sum else None
+    if use_sum:
+        want_dx = [False] * len(opts)
     h = pick([dp.h for dp in dps], save_h)
     plora.plora_group_fwd(group, dps[0].x, [dp.W for dp in dps], [dp.A for dp in dps], [dp.B for dp in dps],
                           [dp.y for dp in dps], h, ws)
     plora.plora_group_bwd(group, dps[0].x, [dp.W for dp in dps], [dp.A for dp in dps], [dp.B for dp in dps],
                           [dp.dy for dp in dps], h, pick([dp.dx for dp in dps], want_dx), pick([dp.dA for dp in dps], want_w),
-                          pick([dp.dB for dp in dps], want_w), ws)
+                          pick([dp.dB for dp in dps], want_w), ws, dx_sum=dx_sum)
     torch.cuda.synchronize()
     for name, base, nbytes in guards:
         assert bool((base[:gh.GUARD_BYTES] == gh.GUARD_BYTE).all()) and bool((base[gh.GUARD_BYTES + nbytes:] == gh.GUARD_BYTE).all()), name
+    dx_total = np.zeros((lay.T, lins[0].D), dtype=np.float64)
     for p, (lin, t, dp) in enumerate(zip(lins, tens, dps)):
         gh.check_guards(dp)
         prob = make_problem(oracle, lin, t)
         y_o, h_o = oracle.loops.forward(prob)
         dx_o, _, dA_o, dB_o = oracle.loops.backward(prob, t.dy)
+        dx_total += dx_o
         errs = {}
         if lay.T:
             errs["y"] = scaled_err(gh.to_np(dp.y), y_o)
@@ -187,3 +195,6 @@ def test_generated_ragged_groups(case):
                 assert bool(dp.dA[k].isnan().all()) and bool(dp.dB[k].isnan().all()), (p, k, "gradients written")
         for k, v in errs.items():
             assert np.isfinite(v) and v <= TOL["bf16"], (lin.name, p, k, v)
+    if use_sum and lay.T:
+        v = scaled_err(gh.to_np(dx_sum), dx_total)
+        assert np.isfinite(v) and v <= TOL["bf16"], ("dx_sum", v)

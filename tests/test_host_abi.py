@@ -183,11 +183,13 @@ def test_grouped_calls_reject_before_touching_the_device():
     assert fwd(0x1000, Wp, ABp, ABp, yp, 0x1010, gw) == 6
     assert fwd(0x1000, Wp, ABp, ABp, two(0x3000, 0x4004), 0x1000, gw) == 6          # second projection's y misaligned
     assert fwd(0x1000, Wp, ABp, ABp, two(0x3000, None), 0x1000, gw) == 1
-    bwd = lambda dy, dx, dA, dB: L.plora_group_bwd(g.ref, 0x1000, Wp, ABp, ABp, dy, None, dx, dA, dB, 0x1000, gw, None)
+    bwd = lambda dy, dx, dA, dB, dx_sum=None: L.plora_group_bwd(g.ref, 0x1000, Wp, ABp, ABp, dy, None, dx, dx_sum, dA, dB, 0x1000, gw, None)
     assert bwd(None, None, None, None) == 1
     assert bwd(two(0x1000, None), None, None, None) == 1
     assert bwd(yp, None, ABp, None) == 1                                          # dA without dB
     assert bwd(yp, two(0x1000, 0x1008), None, None) == 6
+    assert bwd(yp, two(0x1000, 0x2000), None, None, 0x3000) == 11                  # dx and dx_sum: one or the other
+    assert bwd(yp, None, None, None, 0x3004) == 6
 
 
 @pytest.mark.parametrize("seed", range(6))
