@@ -262,27 +262,40 @@ def main():
             plora.plora_group_fwd(g, rs[0].xs[i % rs[0].n_sets], [r.W for r in rs], [r.A for r in rs], [r.B for r in rs],
                                   [r.y for r in rs], [r.h for r in rs], ws)
 
-        def gbwd(gr, i):
+        def gbwd(gr, i, summed=False):
             g, ws, rs = gr
             plora.plora_group_bwd(g, rs[0].xs[i % rs[0].n_sets], [r.W_bwd for r in rs], [r.A for r in rs], [r.B for r in rs],
-                                  [r.dys[i % r.n_sets] for r in rs], [r.h for r in rs], [r.dx for r in rs],
-                                  [r.dA for r in rs], [r.dB for r in rs], ws)
+                                  [r.dys[i % r.n_sets] for r in rs], [r.h for r in rs], None if summed else [r.dx for r in rs],
+                                  [r.dA for r in rs], [r.dB for r in rs], ws, dx_sum=rs[0].dx if summed else None)
 
         if len(runs) != 7:
-            return plain, None
+            return plain, None, None, None
         qkv, gate_up = group_of((0, 1, 2)), group_of((4, 5))
 
         def grouped(i):
             gfwd(qkv, i); runs[3].fwd(i); gfwd(gate_up, i); runs[6].fwd(i)
             runs[6].bwd(i); gbwd(gate_up, i); runs[3].bwd(i); gbwd(qkv, i)
 
-        return plain, grouped
+        # the layer as a model runs it: the gradient of a shared input is the sum over the projections that read it.
+        # Plain calls leave that to two elementwise additions for q / k / v and one for gate / up; the grouped calls
+        # form it in the GEMM epilogues (dx_sum).
+        def plain_summed(i):
+            plain(i)
+            torch.add(runs[4].dx, runs[5].dx, out=runs[4].dx)
+            torch.add(runs[0].dx, runs[1].dx, out=runs[0].dx)
+            torch.add(runs[0].dx, runs[2].dx, out=runs[0].dx)
+
+        def grouped_summed(i):
+            gfwd(qkv, i); runs[3].fwd(i); gfwd(gate_up, i); runs[6].fwd(i)
+            runs[6].bwd(i); gbwd(gate_up, i, True); runs[3].bwd(i); gbwd(qkv, i, True)
+
+        return plain, grouped, plain_summed, grouped_summed
 
     if args.linear < 0:
         # profiling mode: the linears of the configuration back to back (--grouped: q / k / v and gate / up as grouped calls)
         lins = wl.config(args.config)
         runs = [Runner(l, None, seed=1000 * args.config + i) for i, l in enumerate(lins)]
-        plain_step, grouped_step = layer_steps(runs)
+        plain_step, grouped_step, _, _ = layer_steps(runs)
         if args.grouped and grouped_step is None:
             raise SystemExit("--grouped needs the seven linears of configuration 4")
         layer_step = grouped_step if args.grouped else plain_step
@@ -563,9 +576,11 @@ def main():
                     torch.cuda.empty_cache()
             if cfg == 4:
                 runs = [r for _, r, _ in entries]
-                layer_step, grouped_step = layer_steps(runs)
+                layer_step, grouped_step, plain_summed, grouped_summed = layer_steps(runs)
                 ms4 = timed(layer_step, n_pc, 3)
                 ms4g = timed(grouped_step, n_pc, 3)
+                ms4ps = timed(plain_summed, n_pc, 3)
+                ms4gs = timed(grouped_summed, n_pc, 3)
                 # the same layer on one configuration's own small batch (512 tokens, one adapter): with the full batch it
                 # gives the planner's cost model, time(tokens) = floor + slope * tokens
                 small_T = 512
@@ -588,6 +603,12 @@ def main():
                                                "ms_per_step_in_kernel": {k: {"plain_7_launches": round(7 * kp[k], 4),
                                                                              "grouped_4_launches": round(4 * kg[k], 4)}
                                                                          for k in ("shrink", "da") if kp.get(k) and kg.get(k)},
+                                               "with_input_gradients_summed": {
+                                                   "plain_calls_plus_three_additions_ms": round(ms4ps, 4),
+                                                   "grouped_dx_sum_ms": round(ms4gs, 4),
+                                                   "note": "the gradient of a shared input is the sum over the projections that read "
+                                                           "it: plain calls plus torch.add (two for q/k/v, one for gate/up) against "
+                                                           "the grouped calls' dx_sum (summed in the GEMM epilogues)"},
                                                "note": "plora_group_fwd / _bwd for q,k,v (one x) and gate,up (one x): one "
                                                        "shrink pass and one dA pass over x per group; o and down as plain calls"},
                                    "linears": [e for _, _, e in entries]})

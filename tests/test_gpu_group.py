@@ -207,6 +207,15 @@ def test_config4_groups_full_size(members):
         assert torch.equal(ref.h[:nh], dp.h[:nh]) and torch.equal(ref.y, dp.y) and torch.equal(ref.dx, dp.dx), lin.name
         del ref
         torch.cuda.empty_cache()
+    # the summed input gradient at full size: the chain of bf16 additions of the per-projection results, bit for bit
+    chain = dps[0].dx.clone()
+    for dp in dps[1:]:
+        chain = chain + dp.dx
+    dx_sum = torch.full_like(chain, float("nan"))
+    plora.plora_group_bwd(group, x, [dp.W for dp in dps], [dp.A for dp in dps], [dp.B for dp in dps], [dp.dy for dp in dps],
+                          [dp.h for dp in dps], None, None, None, ws, dx_sum=dx_sum)
+    torch.cuda.synchronize()
+    assert torch.equal(dx_sum, chain)
 
 
 @pytest.mark.parametrize("case", ["qkv_one_pass", "cut_in_two", "four", "gate_up", "f32", "single"])
