@@ -532,6 +532,18 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
     // tile does not touch) and stores whole 128-byte rows, 16 bytes per lane.
     {
         char *stg = lds + (grp == 0 ? kWA : kWB) + 2 * GR + w4 * 4096;
+        // ACC: what the tile holds so far, all 16 pieces of this lane requested before the first is needed
+        uint4 old[ACC ? 16 : 1];
+        if constexpr (ACC) {
+#pragma unroll
+            for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int row = (lane >> 3) + 8 * j, c = lane & 7;
+                    const int m = em0 + wm0 + mi * 32 + row, n = en0 + wn0 + c * 8;
+                    old[mi * 4 + j] = (m < M && n < N) ? *reinterpret_cast<const uint4 *>(Cout + (int64_t)m * N + n) : uint4{0u, 0u, 0u, 0u};
+                }
+        }
 #pragma unroll
         for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
@@ -551,10 +563,10 @@ __global__ void __launch_bounds__(512) k_gemm(const GemmTile *__restrict__ tiles
                 const int m = em0 + wm0 + mi * 32 + row, n = en0 + wn0 + c * 8;
                 if (m < M && n < N) {
                     if constexpr (ACC) {
-                        const uint4 old = *reinterpret_cast<const uint4 *>(Cout + (int64_t)m * N + n);
+                        const uint4 o = old[mi * 4 + j];
                         uint4 sum;
-                        sum.x = add_bf16x2(old.x, v.x); sum.y = add_bf16x2(old.y, v.y);
-                        sum.z = add_bf16x2(old.z, v.z); sum.w = add_bf16x2(old.w, v.w);
+                        sum.x = add_bf16x2(o.x, v.x); sum.y = add_bf16x2(o.y, v.y);
+                        sum.z = add_bf16x2(o.z, v.z); sum.w = add_bf16x2(o.w, v.w);
                         *reinterpret_cast<uint4 *>(Cout + (int64_t)m * N + n) = sum;
                     } else {
                         *reinterpret_cast<uint4 *>(Cout + (int64_t)m * N + n) = v;
